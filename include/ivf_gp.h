@@ -1,0 +1,179 @@
+/*
+ * ivf_gp.h — C ABI of the MI355X (gfx950) library for the batched query path
+ * of the inverted index with grouping and pruning
+ * ("Revisiting the Inverted Indices for Billion-Scale Approximate Nearest
+ * Neighbors", Section 2 and Section 3.2).
+ *
+ * Conventions
+ *   - Every array pointer is a DEVICE pointer unless its comment says "host".
+ *   - The caller owns every buffer it passes.  The library owns the opaque
+ *     index handle (its private copy of the index and its scratch memory).
+ *   - Work is enqueued on the HIP stream passed as `void *hip_stream`
+ *     (NULL = the default stream); calls return without waiting for it unless
+ *     stated otherwise.
+ *   - Return value 0 = success, negative = error (see IVF_E*).  Nothing throws
+ *     across this boundary.  On error no output buffer has been written and
+ *     ivf_last_error() describes the failure (thread-local, host string).
+ *   - Row-major everywhere.  D is a multiple of 4 and of M; M is 8 or 16.
+ */
+#ifndef IVF_GP_H
+#define IVF_GP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define IVF_OK      0
+#define IVF_EINVAL -1   /* bad argument (null pointer, size or parameter out of range) */
+#define IVF_ENOMEM -2   /* device or host allocation failed */
+#define IVF_EHIP   -3   /* a HIP runtime call failed */
+
+/* limits of this build */
+#define IVF_MAX_K_RESULTS 1024   /* k of ivf_search */
+#define IVF_MAX_D         1024
+
+typedef struct ivf_index ivf_index; /* opaque */
+
+/*
+ * The trained and encoded index as flat arrays (host struct of device
+ * pointers).  Regions are the Voronoi cells of `centroids` (Section 2,
+ * IVFADC).  Region r has L subregions; subregion l is the Voronoi cell of the
+ * subcentroid c_r + alpha_r (s_l - c_r), s_l = centroids[nbr[r][l]]
+ * (Section 3.2, "The model", Eq. (2)).  Points are stored grouped: all points
+ * of subregion (r, l) are contiguous, subregions in order of r*L + l, and
+ * sub_offsets[r*L + l] is the position of the first one ("we store only the
+ * subregion sizes", here as their prefix sums).  A point's record is the M
+ * PQ bytes of its displacement from its subcentroid (Eq. (4)) plus one byte
+ * indexing const_table, the 256-level quantisation of the query-independent
+ * term of Eq. (6), 2<mu, r> + ||r||^2 (mu the subcentroid, r the decoded
+ * displacement).
+ */
+typedef struct ivf_index_desc {
+    int32_t D;                   /* dimensionality */
+    int32_t M;                   /* PQ bytes per point */
+    int32_t L;                   /* neighbours (= subregions) per region */
+    int64_t K;                   /* regions */
+    int64_t N;                   /* stored points, N < 2^32 */
+    const float    *centroids;   /* [K][D] */
+    const int32_t  *nbr;         /* [K][L] neighbour centroid ids, self excluded */
+    const float    *alpha;       /* [K]    scaling factor per region */
+    const float    *cs_dist2;    /* [K][L] ||c_r - s_l||^2 */
+    const float    *pq_codebook; /* [M][256][D/M] */
+    const float    *const_table; /* [256] ascending */
+    const uint32_t *sub_offsets; /* [K*L + 1] */
+    const uint8_t  *codes;       /* [N][M], grouped order */
+    const uint8_t  *const_byte;  /* [N],    grouped order */
+    const int32_t  *ids;         /* [N] point id of each grouped position, >= 0 */
+} ivf_index_desc;
+
+/*
+ * Build a search handle from a trained + encoded index.  The library makes its
+ * own device copy of everything it needs (codes and constant bytes are
+ * re-laid out into 64-byte aligned per-subregion blocks; the Eq. (7) constant
+ * -alpha(1-alpha)||c - s_l||^2 is tabulated per (region, neighbour), "precomputed
+ * offline and stored explicitly for each neighboring centroid"), so the
+ * caller may free its arrays once the call has returned.  Runs on `hip_stream` and
+ * waits for it.  codes / const_byte / ids / sub_offsets may not be NULL here.
+ */
+int ivf_load_index(const ivf_index_desc *desc, void *hip_stream, ivf_index **out);
+
+/* Release the handle and all device memory it owns (waits for the device). */
+void ivf_free_index(ivf_index *index);
+
+/*
+ * Upper bound in bytes for the scratch the handle may hold for the
+ * query-by-centroid distance tile of stage 1 (default 8 GiB).  Larger batches
+ * are processed in several tiles of queries.  Host call.
+ */
+int ivf_set_scratch_limit(ivf_index *index, int64_t bytes);
+
+/*
+ * Batched search (Section 3.2: "Distance estimation" and "Subregions
+ * pruning").  For each of the nq queries [nq][D]:
+ *   1. squared distances to all K centroids; the nprobe closest regions by
+ *      (distance, centroid id)                               [Section 3.1]
+ *   2. for each probed region and each of its L neighbours the distance to
+ *      the subcentroid, (1-a)||q-c||^2 + a||q-s_l||^2 - a(1-a)||c-s_l||^2,
+ *      reusing the stage-1 distances                          [Eq. (7)]
+ *   3. keep the S = ceil(prune_frac * nprobe * L) closest subregions, chosen
+ *      over all nprobe*L at once, by (distance, r*L + l)      [pruning]
+ *   4. table T[m][j] = -2 <q_m, r^m_j>                        [Eq. (6)]
+ *   5. for every point of every kept subregion the estimate
+ *      score + sum_m T[m][code[m]] + const_table[byte]        [Eq. (6)]
+ *   6. the k smallest by (estimate, id), ascending.
+ * out_ids [nq][k] int32 and out_dists [nq][k] fp32 (estimated squared L2
+ * distance); rows with fewer than k candidates are padded with id -1 and
+ * +inf.  1 <= nprobe <= min(K, 4096), 0 < prune_frac <= 1,
+ * 1 <= k <= IVF_MAX_K_RESULTS, nprobe*L <= 2^20.  All arithmetic is fp32.
+ * Asynchronous on hip_stream; the handle's scratch is reused by every call,
+ * so calls on one handle must not overlap.
+ */
+int ivf_search(ivf_index *index, const float *queries, int64_t nq, int nprobe, float prune_frac,
+               int k, int32_t *out_ids, float *out_dists, void *hip_stream);
+
+/*
+ * ivf_search that also exports the intermediate results of stages 1, 3 and 5
+ * (any of the four pointers may be NULL):
+ *   probe_id  [nq][nprobe] int32, probe_d [nq][nprobe] fp32 — stage 1, in
+ *             ascending centroid id
+ *   kept_sub  [nq][S] int64 subregion ids r*L + l — stage 3, ascending
+ *   n_scanned [nq] int64 — number of point records read in stage 5
+ */
+int ivf_search_stages(ivf_index *index, const float *queries, int64_t nq, int nprobe,
+                      float prune_frac, int k, int32_t *out_ids, float *out_dists,
+                      int32_t *probe_id, float *probe_d, int64_t *kept_sub, int64_t *n_scanned,
+                      void *hip_stream);
+
+/* S of stage 3 for the given parameters (host call, no device work). */
+int64_t ivf_num_kept(int nprobe, int L, float prune_frac);
+
+/*
+ * Stage 1 alone (exhaustive assignment, Section 3.1): the P nearest of the K
+ * centroids [K][D] for each of the nq vectors x [nq][D], by (distance, id),
+ * written in ascending centroid id: out_id [nq][P], out_d [nq][P] squared
+ * distances.  Used for query assignment, for assigning points to regions
+ * (P = 1) and for the neighbour table NN_L (Eq. (2)).  Allocates and frees its
+ * own scratch (waits for the stream).
+ */
+int ivf_coarse_topk(const float *centroids, int64_t K, int D, const float *x, int64_t nq, int P,
+                    int32_t *out_id, float *out_d, void *hip_stream);
+
+/*
+ * Index-time encoding of n points x [n][D] (Section 3.2): region = nearest
+ * centroid (or, if `region_in` is given, that region is taken as is —
+ * approximate / externally computed assignment, Section 3.1), subregion by
+ * Eq. (3), displacement from the subcentroid by Eq. (4), PQ code of the
+ * displacement (Section 2), the per-point term t = 2<mu, r> + ||r||^2 of
+ * Eq. (6) and its nearest entry in const_table (lower index on ties).
+ * Only the trained fields of `trained` are read (centroids, nbr, alpha,
+ * cs_dist2, pq_codebook, const_table; const_table may be NULL, then
+ * out_const_byte is not written).  Outputs: out_region [n] int32, out_sub [n]
+ * int32, out_codes [n][M], out_const_byte [n], out_const_t [n] fp32 (may be
+ * NULL).  Waits for the stream.
+ */
+int ivf_encode(const ivf_index_desc *trained, const float *x, int64_t n, const int32_t *region_in,
+               int32_t *out_region, int32_t *out_sub, uint8_t *out_codes, uint8_t *out_const_byte,
+               float *out_const_t, void *hip_stream);
+
+/*
+ * Training statistics for alpha (Section 3.2, Eqs. (11)-(12)): for each of the
+ * n training points x [n][D] with region[n], pick the neighbour s_l whose
+ * line through c leaves the smallest residual with the coefficient clamped to
+ * [0,1] (Eq. (10)-(11)), and accumulate num[r] += (x-c)^T(s_l-c),
+ * den[r] += ||s_l-c||^2 into the caller's zero-initialised fp64 arrays
+ * num[K], den[K]; alpha_r = num[r]/den[r] (Eq. (12)) is left to the caller.
+ * Asynchronous on hip_stream.
+ */
+int ivf_alpha_stats(const float *centroids, int64_t K, int D, const int32_t *nbr, int L,
+                    const float *x, int64_t n, const int32_t *region, double *num, double *den,
+                    void *hip_stream);
+
+/* Message of the last error on this host thread ("" if none). */
+const char *ivf_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IVF_GP_H */

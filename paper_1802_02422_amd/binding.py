@@ -1,0 +1,247 @@
+"""ctypes binding with the same names as the C ABI (``include/ivf_gp.h``).
+
+Tensors are torch CUDA(HIP) tensors used purely as device buffers: the binding
+checks dtype / device / contiguity, passes ``data_ptr()`` and the current
+stream handle, and allocates output tensors.  Every step of the method runs in
+the library's kernels.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libivf_gp.so")
+_lib = None
+
+
+class IvfError(RuntimeError):
+    pass
+
+
+class _Desc(C.Structure):
+    _fields_ = [("D", C.c_int32), ("M", C.c_int32), ("L", C.c_int32), ("K", C.c_int64), ("N", C.c_int64),
+                ("centroids", C.c_void_p), ("nbr", C.c_void_p), ("alpha", C.c_void_p),
+                ("cs_dist2", C.c_void_p), ("pq_codebook", C.c_void_p), ("const_table", C.c_void_p),
+                ("sub_offsets", C.c_void_p), ("codes", C.c_void_p), ("const_byte", C.c_void_p),
+                ("ids", C.c_void_p)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the built HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise IvfError(f"{_LIB_PATH} is missing: build it first (python -m paper_1802_02422_amd.build); "
+                       "there is no fallback path")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i64, i32, f32 = C.c_void_p, C.c_int64, C.c_int, C.c_float
+    lib.ivf_load_index.argtypes = [C.POINTER(_Desc), vp, C.POINTER(vp)]
+    lib.ivf_free_index.argtypes = [vp]
+    lib.ivf_free_index.restype = None
+    lib.ivf_set_scratch_limit.argtypes = [vp, i64]
+    lib.ivf_search.argtypes = [vp, vp, i64, i32, f32, i32, vp, vp, vp]
+    lib.ivf_search_stages.argtypes = [vp, vp, i64, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.ivf_num_kept.argtypes = [i32, i32, f32]
+    lib.ivf_num_kept.restype = i64
+    lib.ivf_coarse_topk.argtypes = [vp, i64, i32, vp, i64, i32, vp, vp, vp]
+    lib.ivf_encode.argtypes = [C.POINTER(_Desc), vp, i64, vp, vp, vp, vp, vp, vp, vp]
+    lib.ivf_alpha_stats.argtypes = [vp, i64, i32, vp, i32, vp, i64, vp, vp, vp, vp]
+    lib.ivf_last_error.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def ivf_last_error() -> str:
+    return load_library().ivf_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise IvfError(f"ivf error {rc}: {ivf_last_error()}")
+
+
+def _dev(t: Optional[torch.Tensor], dtype, name: str, shape=None):
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise IvfError(f"{name} must be a device tensor")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise IvfError(f"{name} must be contiguous {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise IvfError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    return t
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+@dataclass
+class IndexDesc:
+    """Device tensors of the trained (+ optionally encoded) index, mirroring ``ivf_index_desc``."""
+    centroids: torch.Tensor                      # [K, D] fp32
+    nbr: torch.Tensor                            # [K, L] int32
+    alpha: torch.Tensor                          # [K] fp32
+    cs_dist2: torch.Tensor                       # [K, L] fp32
+    pq_codebook: torch.Tensor                    # [M, 256, D/M] fp32
+    const_table: Optional[torch.Tensor] = None   # [256] fp32
+    sub_offsets: Optional[torch.Tensor] = None   # [K*L+1] uint32 bit patterns (int32 / int64 accepted)
+    codes: Optional[torch.Tensor] = None         # [N, M] uint8
+    const_byte: Optional[torch.Tensor] = None    # [N] uint8
+    ids: Optional[torch.Tensor] = None           # [N] int32
+
+    def _c(self) -> _Desc:
+        K, D = self.centroids.shape
+        L = self.nbr.shape[1]
+        M = self.pq_codebook.shape[0]
+        _dev(self.centroids, torch.float32, "centroids")
+        _dev(self.nbr, torch.int32, "nbr", (K, L))
+        _dev(self.alpha, torch.float32, "alpha", (K,))
+        _dev(self.cs_dist2, torch.float32, "cs_dist2", (K, L))
+        _dev(self.pq_codebook, torch.float32, "pq_codebook", (M, 256, D // M))
+        _dev(self.const_table, torch.float32, "const_table", (256,))
+        N = 0
+        if self.codes is not None:
+            N = self.codes.shape[0]
+            _dev(self.codes, torch.uint8, "codes", (N, M))
+            _dev(self.const_byte, torch.uint8, "const_byte", (N,))
+            _dev(self.ids, torch.int32, "ids", (N,))
+            if self.sub_offsets is None or self.sub_offsets.dtype not in (torch.int32, torch.uint32):
+                raise IvfError("sub_offsets must be a 32-bit tensor of K*L+1 entries")
+            _dev(self.sub_offsets, self.sub_offsets.dtype, "sub_offsets", (K * L + 1,))
+        return _Desc(D, M, L, K, N, *[None if t is None else t.data_ptr() for t in (
+            self.centroids, self.nbr, self.alpha, self.cs_dist2, self.pq_codebook, self.const_table,
+            self.sub_offsets, self.codes, self.const_byte, self.ids)])
+
+
+class IndexHandle:
+    def __init__(self, ptr, desc: IndexDesc):
+        self.ptr = ptr
+        self.K, self.D = desc.centroids.shape
+        self.L = desc.nbr.shape[1]
+        self.M = desc.pq_codebook.shape[0]
+        self.N = desc.codes.shape[0]
+
+    def __del__(self):
+        try:
+            ivf_free_index(self)
+        except Exception:
+            pass
+
+
+def ivf_load_index(desc: IndexDesc) -> IndexHandle:
+    lib = load_library()
+    out = C.c_void_p()
+    _check(lib.ivf_load_index(C.byref(desc._c()), _stream(), C.byref(out)))
+    return IndexHandle(out, desc)
+
+
+def ivf_free_index(index: IndexHandle) -> None:
+    if index.ptr is not None:
+        load_library().ivf_free_index(index.ptr)
+        index.ptr = None
+
+
+def ivf_set_scratch_limit(index: IndexHandle, nbytes: int) -> None:
+    _check(load_library().ivf_set_scratch_limit(index.ptr, nbytes))
+
+
+def ivf_num_kept(nprobe: int, L: int, prune_frac: float) -> int:
+    return int(load_library().ivf_num_kept(nprobe, L, prune_frac))
+
+
+def ivf_search(index: IndexHandle, queries: torch.Tensor, nprobe: int, prune_frac: float, k: int,
+               out_ids: Optional[torch.Tensor] = None, out_dists: Optional[torch.Tensor] = None):
+    """(ids [nq, k] int32, dists [nq, k] fp32); asynchronous on the current stream."""
+    nq = queries.shape[0]
+    _dev(queries, torch.float32, "queries", (nq, index.D))
+    if out_ids is None:
+        out_ids = torch.empty((nq, k), dtype=torch.int32, device=queries.device)
+    if out_dists is None:
+        out_dists = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+    _dev(out_ids, torch.int32, "out_ids", (nq, k))
+    _dev(out_dists, torch.float32, "out_dists", (nq, k))
+    _check(load_library().ivf_search(index.ptr, _ptr(queries), nq, nprobe, prune_frac, k,
+                                     _ptr(out_ids), _ptr(out_dists), _stream()))
+    return out_ids, out_dists
+
+
+def ivf_search_stages(index: IndexHandle, queries: torch.Tensor, nprobe: int, prune_frac: float, k: int):
+    """ivf_search plus the stage-1 probes, the kept subregions and the scanned-record counts."""
+    nq = queries.shape[0]
+    _dev(queries, torch.float32, "queries", (nq, index.D))
+    dev = queries.device
+    S = ivf_num_kept(nprobe, index.L, prune_frac)
+    out = {
+        "ids": torch.empty((nq, k), dtype=torch.int32, device=dev),
+        "dists": torch.empty((nq, k), dtype=torch.float32, device=dev),
+        "probe_id": torch.empty((nq, nprobe), dtype=torch.int32, device=dev),
+        "probe_d": torch.empty((nq, nprobe), dtype=torch.float32, device=dev),
+        "kept_sub": torch.empty((nq, S), dtype=torch.int64, device=dev),
+        "n_scanned": torch.empty((nq,), dtype=torch.int64, device=dev),
+    }
+    _check(load_library().ivf_search_stages(
+        index.ptr, _ptr(queries), nq, nprobe, prune_frac, k, _ptr(out["ids"]), _ptr(out["dists"]),
+        _ptr(out["probe_id"]), _ptr(out["probe_d"]), _ptr(out["kept_sub"]), _ptr(out["n_scanned"]),
+        _stream()))
+    return out
+
+
+def ivf_coarse_topk(centroids: torch.Tensor, x: torch.Tensor, P: int):
+    """(ids [n, P] int32 ascending centroid id, squared distances [n, P] fp32)."""
+    K, D = centroids.shape
+    n = x.shape[0]
+    _dev(centroids, torch.float32, "centroids")
+    _dev(x, torch.float32, "x", (n, D))
+    oid = torch.empty((n, P), dtype=torch.int32, device=x.device)
+    od = torch.empty((n, P), dtype=torch.float32, device=x.device)
+    _check(load_library().ivf_coarse_topk(_ptr(centroids), K, D, _ptr(x), n, P, _ptr(oid), _ptr(od), _stream()))
+    return oid, od
+
+
+def ivf_encode(trained: IndexDesc, x: torch.Tensor, region_in: Optional[torch.Tensor] = None,
+               want_t: bool = False):
+    """(region, sub, codes, const_byte, t) for the points x [n, D]."""
+    n = x.shape[0]
+    c = trained._c()
+    _dev(x, torch.float32, "x", (n, c.D))
+    _dev(region_in, torch.int32, "region_in", (n,))
+    dev = x.device
+    region = torch.empty(n, dtype=torch.int32, device=dev)
+    sub = torch.empty(n, dtype=torch.int32, device=dev)
+    codes = torch.empty((n, c.M), dtype=torch.uint8, device=dev)
+    byte = torch.empty(n, dtype=torch.uint8, device=dev) if trained.const_table is not None else None
+    t = torch.empty(n, dtype=torch.float32, device=dev) if want_t else None
+    _check(load_library().ivf_encode(C.byref(c), _ptr(x), n, _ptr(region_in), _ptr(region), _ptr(sub),
+                                     _ptr(codes), _ptr(byte), _ptr(t), _stream()))
+    return region, sub, codes, byte, t
+
+
+def ivf_alpha_stats(centroids: torch.Tensor, nbr: torch.Tensor, x: torch.Tensor, region: torch.Tensor,
+                    num: torch.Tensor, den: torch.Tensor) -> None:
+    """Accumulate the numerator / denominator sums of the alpha estimate into num, den [K] fp64."""
+    K, D = centroids.shape
+    L = nbr.shape[1]
+    n = x.shape[0]
+    _dev(centroids, torch.float32, "centroids")
+    _dev(nbr, torch.int32, "nbr", (K, L))
+    _dev(x, torch.float32, "x", (n, D))
+    _dev(region, torch.int32, "region", (n,))
+    _dev(num, torch.float64, "num", (K,))
+    _dev(den, torch.float64, "den", (K,))
+    _check(load_library().ivf_alpha_stats(_ptr(centroids), K, D, _ptr(nbr), L, _ptr(x), n, _ptr(region),
+                                          _ptr(num), _ptr(den), _stream()))

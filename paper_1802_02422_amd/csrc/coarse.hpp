@@ -1,0 +1,133 @@
+// Stage 1: squared distances from a tile of queries to all K centroids as an
+// fp32 MFMA GEMM (||q||^2 - 2<q,c> + ||c||^2), and the exact per-query
+// selection of the nprobe closest regions (exhaustive assignment, Section 3.1).
+#pragma once
+#include "select.hpp"
+
+namespace ivf {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// ||row||^2 of an [n][D] fp32 matrix, one wavefront per row.
+__global__ __launch_bounds__(256) void row_norm_kernel(const float *__restrict__ X, int64_t n,
+                                                       int D, float *__restrict__ out)
+{
+    int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    int lane = threadIdx.x & 63;
+    if (row >= n) return;
+    float s = 0.f;
+    for (int i = lane; i < D; i += WAVE) {
+        float v = X[row * D + i];
+        s = fmaf(v, v, s);
+    }
+    s = wave_sum(s);
+    if (lane == 0) out[row] = s;
+}
+
+constexpr int GT = 128;        // tile: GT queries x GT centroids per workgroup
+constexpr int GKC = 32;        // dimensions staged per step
+constexpr int GLD = GKC + 4;   // LDS row stride in floats (keeps 16-byte alignment, spreads banks)
+
+// Dt[q][j] = max(0, qn[q] + cn[j] - 2 <Q[q], C[j]>) for one 128x128 tile per
+// workgroup of 4 wavefronts; each wavefront owns a 64x64 quadrant as 2x2
+// v_mfma_f32_32x32x2f32 accumulators.  Within a 32-dim stage lane half h
+// feeds dims [16h, 16h+16) to both operands, so one ds_read_b128 serves four
+// MFMA steps (the order of the k-summation is free).
+// Tiles are numbered centroid-tile-major so that the query tiles (small, L2
+// resident) are swept against one centroid tile after the other.
+__global__ __launch_bounds__(256) void coarse_gemm_kernel(
+    const float *__restrict__ Q, const float *__restrict__ qn, int64_t nq,
+    const float *__restrict__ C, const float *__restrict__ cn, int64_t K, int D,
+    float *__restrict__ Dt, int tiles_q)
+{
+    __shared__ __attribute__((aligned(16))) float As[GT * GLD];
+    __shared__ __attribute__((aligned(16))) float Bs[GT * GLD];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int64_t tile = blockIdx.x;
+    const int64_t q0 = (tile % tiles_q) * GT, c0 = (tile / tiles_q) * GT;
+    const int wq = (wave >> 1) * 64, wc = (wave & 1) * 64;
+    const int l32 = lane & 31, h = lane >> 5;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    for (int k0 = 0; k0 < D; k0 += GKC) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            int idx = tid + it * 256;
+            int row = idx >> 3, c4 = (idx & 7) * 4;
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+            if (k0 + c4 < D) {
+                if (q0 + row < nq) a = *reinterpret_cast<const float4 *>(Q + (q0 + row) * D + k0 + c4);
+                if (c0 + row < K) b = *reinterpret_cast<const float4 *>(C + (c0 + row) * D + k0 + c4);
+            }
+            *reinterpret_cast<float4 *>(&As[row * GLD + c4]) = a;
+            *reinterpret_cast<float4 *>(&Bs[row * GLD + c4]) = b;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+            float4 a[2], b[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                a[i] = *reinterpret_cast<const float4 *>(&As[(wq + i * 32 + l32) * GLD + h * 16 + s4 * 4]);
+                b[i] = *reinterpret_cast<const float4 *>(&Bs[(wc + i * 32 + l32) * GLD + h * 16 + s4 * 4]);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b[j].x, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b[j].y, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b[j].z, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b[j].w, acc[i][j], 0, 0, 0);
+                }
+        }
+        __syncthreads();
+    }
+
+    // accumulator element v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        int64_t col = c0 + wc + j * 32 + l32;
+        if (col >= K) continue;
+        float cnj = cn[col];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int64_t row = q0 + wq + i * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (row < nq) {
+                    float d = fmaf(-2.f, acc[i][j][v], qn[row] + cnj);
+                    Dt[row * K + col] = fmaxf(d, 0.f);
+                }
+            }
+    }
+}
+
+// The P closest centroids of each query row of Dt by (distance, id), written
+// in ascending centroid id.  One workgroup per query.
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void probe_select_kernel(const float *__restrict__ Dt, int64_t K,
+                                                             int P, int32_t *__restrict__ probe_id,
+                                                             float *__restrict__ probe_d)
+{
+    __shared__ SelectShared sh;
+    const int64_t q = blockIdx.x;
+    const float *row = Dt + q * K;
+    auto key = [row](int64_t i) { return float_key(row[i]); };
+    uint32_t pivot, need;
+    block_radix_select<BLOCK>(key, K, (uint32_t)P, sh, pivot, need);
+    block_emit_selected<BLOCK>(key, K, (uint32_t)P, pivot, need, sh,
+                               [&](uint32_t pos, int64_t i, uint32_t k) {
+                                   probe_id[q * P + pos] = (int32_t)i;
+                                   probe_d[q * P + pos] = key_float(k);
+                               });
+}
+
+}  // namespace ivf

@@ -1,0 +1,145 @@
+// Index-time kernels: subregion assignment (Eq. (3)), displacement (Eq. (4)),
+// PQ encoding, the per-point constant of Eq. (6), and the statistics for
+// learning alpha (Eqs. (11)-(12)).  One wavefront per point.
+#pragma once
+#include "util.hpp"
+
+namespace ivf {
+
+// LDS per workgroup (one wavefront): x, c and e/mu, each D floats.
+__global__ __launch_bounds__(64) void encode_kernel(
+    const float *__restrict__ X, int64_t n, int D, int M, int L, const int32_t *__restrict__ region,
+    const float *__restrict__ C, const int32_t *__restrict__ nbr, const float *__restrict__ alpha,
+    const float *__restrict__ cs_dist2, const float *__restrict__ codebook,
+    const float *__restrict__ const_table, int32_t *__restrict__ out_sub,
+    uint8_t *__restrict__ out_codes, uint8_t *__restrict__ out_byte, float *__restrict__ out_t)
+{
+    extern __shared__ float sm[];
+    float *xs = sm, *cs = sm + D, *es = sm + 2 * D, *mus = sm + 3 * D;
+    const int lane = threadIdx.x;
+    const int64_t i = blockIdx.x;
+    if (i >= n) return;
+    const int64_t r = region[i];
+    const float a = alpha[r];
+    for (int t = lane; t < D; t += WAVE) {
+        xs[t] = X[i * D + t];
+        cs[t] = C[r * D + t];
+    }
+    wave_sync();
+
+    // Eq. (3) through the closed form of the subcentroid distance:
+    // ||x - mu_l||^2 = (1-a)||x-c||^2 + a||x-s_l||^2 - a(1-a)||c-s_l||^2
+    float dxc = 0.f;
+    for (int t = 0; t < D; ++t) {
+        float u = xs[t] - cs[t];
+        dxc = fmaf(u, u, dxc);
+    }
+    float best = INFINITY;
+    int best_l = 0x7fffffff;
+    for (int l = lane; l < L; l += WAVE) {
+        const float *s = C + (int64_t)nbr[r * L + l] * D;
+        float dxs = 0.f;
+        for (int t = 0; t < D; t += 4) {
+            float4 sv = *reinterpret_cast<const float4 *>(s + t);
+            float u0 = xs[t] - sv.x, u1 = xs[t + 1] - sv.y, u2 = xs[t + 2] - sv.z, u3 = xs[t + 3] - sv.w;
+            dxs = fmaf(u0, u0, dxs);
+            dxs = fmaf(u1, u1, dxs);
+            dxs = fmaf(u2, u2, dxs);
+            dxs = fmaf(u3, u3, dxs);
+        }
+        float sc = fmaf(a, dxs, fmaf(1.f - a, dxc, -a * (1.f - a) * cs_dist2[r * L + l]));
+        if (sc < best) { best = sc; best_l = l; }
+    }
+    wave_argmin(best, best_l);
+    if (lane == 0) out_sub[i] = best_l;
+
+    // Eq. (4): displacement from the chosen subcentroid
+    const float *s = C + (int64_t)nbr[r * L + best_l] * D;
+    for (int t = lane; t < D; t += WAVE) {
+        float mu = fmaf(a, s[t] - cs[t], cs[t]);
+        mus[t] = mu;
+        es[t] = xs[t] - mu;
+    }
+    wave_sync();
+
+    // PQ: nearest of the 256 codewords per block of D/M dims, lowest index on ties
+    const int ds = D / M;
+    float tpart = 0.f;   // lane-partial of 2<mu, r> + ||r||^2
+    for (int m = 0; m < M; ++m) {
+        float bd = INFINITY;
+        int bj = 0x7fffffff;
+        for (int j = lane; j < 256; j += WAVE) {
+            const float *cw = codebook + ((int64_t)m * 256 + j) * ds;
+            float dd = 0.f;
+            for (int t = 0; t < ds; ++t) {
+                float u = es[m * ds + t] - cw[t];
+                dd = fmaf(u, u, dd);
+            }
+            if (dd < bd) { bd = dd; bj = j; }
+        }
+        wave_argmin(bd, bj);
+        if (lane == 0) out_codes[i * M + m] = (uint8_t)bj;
+        const float *cw = codebook + ((int64_t)m * 256 + bj) * ds;
+        for (int t = lane; t < ds; t += WAVE) {
+            float rv = cw[t];
+            tpart = fmaf(2.f * mus[m * ds + t], rv, fmaf(rv, rv, tpart));
+        }
+    }
+    float tval = wave_sum(tpart);
+    if (lane == 0 && out_t) out_t[i] = tval;
+
+    if (const_table) {
+        float bd = INFINITY;
+        int bj = 0x7fffffff;
+        for (int j = lane; j < 256; j += WAVE) {
+            float dd = fabsf(tval - const_table[j]);
+            if (dd < bd) { bd = dd; bj = j; }
+        }
+        wave_argmin(bd, bj);
+        if (lane == 0) out_byte[i] = (uint8_t)bj;
+    }
+}
+
+// Step 1 of alpha learning per training point (Eqs. (10)-(11)) and the two sums
+// of Eq. (12), accumulated per region in fp64.
+__global__ __launch_bounds__(64) void alpha_stats_kernel(
+    const float *__restrict__ X, int64_t n, int D, int L, const int32_t *__restrict__ region,
+    const float *__restrict__ C, const int32_t *__restrict__ nbr, double *__restrict__ num,
+    double *__restrict__ den)
+{
+    extern __shared__ float sm[];
+    float *xc = sm;   // x - c
+    const int lane = threadIdx.x;
+    const int64_t i = blockIdx.x;
+    if (i >= n) return;
+    const int64_t r = region[i];
+    for (int t = lane; t < D; t += WAVE) xc[t] = X[i * D + t] - C[r * D + t];
+    wave_sync();
+    double xc2 = 0.0;
+    for (int t = 0; t < D; ++t) xc2 += (double)xc[t] * (double)xc[t];
+    double best = INFINITY, bdot = 0.0, bn2 = 0.0;
+    int bl = 0x7fffffff;
+    for (int l = lane; l < L; l += WAVE) {
+        const float *s = C + (int64_t)nbr[r * L + l] * D;
+        const float *c = C + r * D;
+        double dot = 0.0, n2 = 0.0;
+        for (int t = 0; t < D; ++t) {
+            double u = (double)s[t] - (double)c[t];
+            dot += (double)xc[t] * u;
+            n2 += u * u;
+        }
+        double a = n2 > 0.0 ? dot / n2 : 0.0;
+        a = a < 0.0 ? 0.0 : (a > 1.0 ? 1.0 : a);
+        double res = xc2 - 2.0 * a * dot + a * a * n2;
+        if (res < best) { best = res; bl = l; bdot = dot; bn2 = n2; }
+    }
+    double wbest = best;
+    int wl = bl;
+    wave_argmin(wbest, wl);
+    if (bl == wl && wl != 0x7fffffff) {   // the single lane holding the winner
+        atomicAdd(&num[r], bdot);
+        atomicAdd(&den[r], bn2);
+    }
+}
+
+}  // namespace ivf

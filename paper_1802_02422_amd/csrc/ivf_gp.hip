@@ -1,0 +1,450 @@
+// C ABI of the library (see include/ivf_gp.h): argument checks, scratch
+// management and the launch sequence of the query path.  gfx950 only.
+#include "../../include/ivf_gp.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include <hip/hip_runtime.h>
+#include <rocprim/device/device_scan.hpp>
+
+#include "coarse.hpp"
+#include "encode.hpp"
+#include "layout.hpp"
+#include "query.hpp"
+#include "scan.hpp"
+
+using namespace ivf;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIPCHK(expr)                                                                         \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return fail(e_ == hipErrorOutOfMemory ? IVF_ENOMEM : IVF_EHIP, "%s: %s", #expr,  \
+                        hipGetErrorString(e_));                                              \
+    } while (0)
+
+#define LAUNCHCHK(name)                                                                      \
+    do {                                                                                     \
+        hipError_t e_ = hipGetLastError();                                                   \
+        if (e_ != hipSuccess) return fail(IVF_EHIP, "launch %s: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+struct Buf {
+    void *p = nullptr;
+    size_t bytes = 0;
+};
+
+int ensure(Buf &b, size_t bytes)
+{
+    if (bytes <= b.bytes) return IVF_OK;
+    if (b.p) {
+        HIPCHK(hipDeviceSynchronize());
+        HIPCHK(hipFree(b.p));
+        b.p = nullptr;
+        b.bytes = 0;
+    }
+    HIPCHK(hipMalloc(&b.p, bytes));
+    b.bytes = bytes;
+    return IVF_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int next_pow2(int v)
+{
+    int p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+int check_trained(const ivf_index_desc *d)
+{
+    if (!d) return fail(IVF_EINVAL, "index descriptor is NULL");
+    if (d->D < 4 || d->D > IVF_MAX_D || d->D % 4) return fail(IVF_EINVAL, "D=%d must be a multiple of 4 in [4, %d]", d->D, IVF_MAX_D);
+    if (d->M != 8 && d->M != 16) return fail(IVF_EINVAL, "M=%d must be 8 or 16", d->M);
+    if (d->D % d->M) return fail(IVF_EINVAL, "D=%d is not a multiple of M=%d", d->D, d->M);
+    if (d->L < 1 || d->K < 1) return fail(IVF_EINVAL, "K=%lld and L=%d must be positive", (long long)d->K, d->L);
+    if ((int64_t)d->L >= d->K && d->K > 1) return fail(IVF_EINVAL, "L=%d needs at least L+1 centroids", d->L);
+    if (d->K * (int64_t)d->L >= (1ll << 31)) return fail(IVF_EINVAL, "K*L must be below 2^31");
+    if (!d->centroids || !d->nbr || !d->alpha || !d->cs_dist2 || !d->pq_codebook)
+        return fail(IVF_EINVAL, "a trained array (centroids, nbr, alpha, cs_dist2, pq_codebook) is NULL");
+    if (!aligned16(d->centroids) || !aligned16(d->pq_codebook))
+        return fail(IVF_EINVAL, "centroids and pq_codebook must be 16-byte aligned");
+    return IVF_OK;
+}
+
+// ------------------------------------------------------------ stage 1 driver
+int launch_coarse(const float *x, const float *xn, int64_t nq, const float *C, const float *cn,
+                  int64_t K, int D, float *Dt, hipStream_t st)
+{
+    int tiles_q = (int)((nq + GT - 1) / GT);
+    int64_t tiles_c = (K + GT - 1) / GT;
+    int64_t grid = tiles_q * tiles_c;
+    if (grid >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
+    coarse_gemm_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(x, xn, nq, C, cn, K, D, Dt, tiles_q);
+    LAUNCHCHK("coarse_gemm_kernel");
+    return IVF_OK;
+}
+
+int launch_probe_select(const float *Dt, int64_t nq, int64_t K, int P, int32_t *pid, float *pd,
+                        hipStream_t st)
+{
+    if (K >= 16384)
+        probe_select_kernel<1024><<<dim3((unsigned)nq), dim3(1024), 0, st>>>(Dt, K, P, pid, pd);
+    else
+        probe_select_kernel<256><<<dim3((unsigned)nq), dim3(256), 0, st>>>(Dt, K, P, pid, pd);
+    LAUNCHCHK("probe_select_kernel");
+    return IVF_OK;
+}
+
+}  // namespace
+
+struct ivf_index {
+    int D = 0, M = 0, L = 0;
+    int64_t K = 0, N = 0;
+    float *centroids = nullptr, *cnorm = nullptr, *alpha = nullptr, *cst = nullptr;
+    float *codebook = nullptr, *const_table = nullptr;
+    int32_t *nbr = nullptr, *ids = nullptr;
+    uint32_t *sub_offsets = nullptr, *blk_off = nullptr;
+    uint8_t *blocks = nullptr;
+    int64_t scratch_limit = 8ll << 30;
+    Buf dt, qn, probe_id, probe_d, scores, desc, lut, partial;
+};
+
+extern "C" const char *ivf_last_error(void) { return g_err.c_str(); }
+
+extern "C" int64_t ivf_num_kept(int nprobe, int L, float prune_frac)
+{
+    int64_t total = (int64_t)nprobe * L;
+    int64_t S = (int64_t)std::ceil((double)prune_frac * (double)nprobe * (double)L);
+    if (S < 1) S = 1;
+    if (S > total) S = total;
+    return S;
+}
+
+extern "C" void ivf_free_index(ivf_index *ix)
+{
+    if (!ix) return;
+    (void)hipDeviceSynchronize();
+    void *owned[] = {ix->centroids, ix->cnorm, ix->alpha, ix->cst, ix->codebook, ix->const_table,
+                     ix->nbr, ix->ids, ix->sub_offsets, ix->blk_off, ix->blocks, ix->dt.p, ix->qn.p,
+                     ix->probe_id.p, ix->probe_d.p, ix->scores.p, ix->desc.p, ix->lut.p, ix->partial.p};
+    for (void *p : owned)
+        if (p) (void)hipFree(p);
+    delete ix;
+}
+
+extern "C" int ivf_set_scratch_limit(ivf_index *ix, int64_t bytes)
+{
+    if (!ix || bytes < 4096) return fail(IVF_EINVAL, "scratch limit must be at least 4096 bytes");
+    ix->scratch_limit = bytes;
+    return IVF_OK;
+}
+
+namespace {
+
+template <class T>
+int dev_copy(T *&dst, const T *src, size_t count, hipStream_t st)
+{
+    HIPCHK(hipMalloc(reinterpret_cast<void **>(&dst), count * sizeof(T) ? count * sizeof(T) : 16));
+    if (count) HIPCHK(hipMemcpyAsync(dst, src, count * sizeof(T), hipMemcpyDeviceToDevice, st));
+    return IVF_OK;
+}
+
+int load_impl(const ivf_index_desc *d, hipStream_t st, ivf_index *ix)
+{
+    const int64_t K = d->K, N = d->N, nsub = K * d->L;
+    const int D = d->D, M = d->M, L = d->L;
+    ix->D = D; ix->M = M; ix->L = L; ix->K = K; ix->N = N;
+    int rc;
+    if ((rc = dev_copy(ix->centroids, d->centroids, (size_t)K * D, st))) return rc;
+    if ((rc = dev_copy(ix->nbr, d->nbr, (size_t)nsub, st))) return rc;
+    if ((rc = dev_copy(ix->alpha, d->alpha, (size_t)K, st))) return rc;
+    if ((rc = dev_copy(ix->codebook, d->pq_codebook, (size_t)256 * D, st))) return rc;
+    if ((rc = dev_copy(ix->const_table, d->const_table, (size_t)256, st))) return rc;
+    if ((rc = dev_copy(ix->sub_offsets, d->sub_offsets, (size_t)nsub + 1, st))) return rc;
+    if ((rc = dev_copy(ix->ids, d->ids, (size_t)N, st))) return rc;
+
+    HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->cnorm), (size_t)K * sizeof(float)));
+    row_norm_kernel<<<dim3((unsigned)((K + 3) / 4)), dim3(256), 0, st>>>(ix->centroids, K, D, ix->cnorm);
+    LAUNCHCHK("row_norm_kernel");
+    HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->cst), (size_t)nsub * sizeof(float)));
+    cst_kernel<<<dim3((unsigned)((nsub + 255) / 256)), dim3(256), 0, st>>>(ix->alpha, d->cs_dist2, L, nsub, ix->cst);
+    LAUNCHCHK("cst_kernel");
+
+    // block offsets: exclusive prefix sum of the block sizes
+    uint32_t *sz = nullptr;
+    HIPCHK(hipMalloc(reinterpret_cast<void **>(&sz), (size_t)nsub * sizeof(uint32_t)));
+    HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->blk_off), (size_t)nsub * sizeof(uint32_t)));
+    blk_size_kernel<<<dim3((unsigned)((nsub + 255) / 256)), dim3(256), 0, st>>>(ix->sub_offsets, nsub, M, sz);
+    LAUNCHCHK("blk_size_kernel");
+    size_t tmp_bytes = 0;
+    HIPCHK(rocprim::exclusive_scan(nullptr, tmp_bytes, sz, ix->blk_off, 0u, (size_t)nsub,
+                                   rocprim::plus<uint32_t>(), st));
+    void *tmp = nullptr;
+    HIPCHK(hipMalloc(&tmp, tmp_bytes ? tmp_bytes : 16));
+    HIPCHK(rocprim::exclusive_scan(tmp, tmp_bytes, sz, ix->blk_off, 0u, (size_t)nsub,
+                                   rocprim::plus<uint32_t>(), st));
+    uint32_t last_off = 0, last_sz = 0;
+    HIPCHK(hipMemcpyAsync(&last_off, ix->blk_off + nsub - 1, 4, hipMemcpyDeviceToHost, st));
+    HIPCHK(hipMemcpyAsync(&last_sz, sz + nsub - 1, 4, hipMemcpyDeviceToHost, st));
+    HIPCHK(hipStreamSynchronize(st));
+    uint64_t total_blk = (uint64_t)last_off + last_sz;
+    // 64-bit check of the 32-bit prefix sum: N*(M+1) bytes plus at most one block of padding each
+    if (((uint64_t)N * (M + 1)) / BLK_ALIGN + (uint64_t)nsub >= (1ull << 32))
+        return fail(IVF_EINVAL, "index too large for 32-bit block offsets");
+    HIPCHK(hipFree(tmp));
+    HIPCHK(hipFree(sz));
+    HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->blocks), (size_t)(total_blk ? total_blk : 1) * BLK_ALIGN));
+    repack_kernel<<<dim3((unsigned)((nsub * 16 + 255) / 256)), dim3(256), 0, st>>>(
+        ix->sub_offsets, ix->blk_off, nsub, M, d->codes, d->const_byte, ix->blocks);
+    LAUNCHCHK("repack_kernel");
+    HIPCHK(hipStreamSynchronize(st));
+    return IVF_OK;
+}
+
+}  // namespace
+
+extern "C" int ivf_load_index(const ivf_index_desc *d, void *hip_stream, ivf_index **out)
+{
+    int rc = check_trained(d);
+    if (rc) return rc;
+    if (!out) return fail(IVF_EINVAL, "out is NULL");
+    if (!d->const_table || !d->sub_offsets || !d->codes || !d->const_byte || !d->ids)
+        return fail(IVF_EINVAL, "an encoded array (const_table, sub_offsets, codes, const_byte, ids) is NULL");
+    if (d->N < 0 || d->N >= (1ll << 32)) return fail(IVF_EINVAL, "N=%lld out of range", (long long)d->N);
+    if (!aligned16(d->codes)) return fail(IVF_EINVAL, "codes must be 16-byte aligned");
+    ivf_index *ix = new (std::nothrow) ivf_index;
+    if (!ix) return fail(IVF_ENOMEM, "host allocation failed");
+    rc = load_impl(d, static_cast<hipStream_t>(hip_stream), ix);
+    if (rc) {
+        std::string keep = g_err;
+        ivf_free_index(ix);
+        g_err = keep;
+        return rc;
+    }
+    *out = ix;
+    return IVF_OK;
+}
+
+extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq, int nprobe,
+                                 float prune_frac, int k, int32_t *out_ids, float *out_dists,
+                                 int32_t *probe_id_out, float *probe_d_out, int64_t *kept_sub_out,
+                                 int64_t *n_scanned_out, void *hip_stream)
+{
+    if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    if (nq < 0 || nq >= (1ll << 31)) return fail(IVF_EINVAL, "nq=%lld out of range", (long long)nq);
+    if (nq == 0) return IVF_OK;
+    if (!queries || !out_ids || !out_dists) return fail(IVF_EINVAL, "queries / out_ids / out_dists is NULL");
+    if (!aligned16(queries)) return fail(IVF_EINVAL, "queries must be 16-byte aligned");
+    if (nprobe < 1 || nprobe > ix->K || nprobe > 4096)
+        return fail(IVF_EINVAL, "nprobe=%d must be in [1, min(K, 4096)]", nprobe);
+    if (!(prune_frac > 0.f) || prune_frac > 1.f) return fail(IVF_EINVAL, "prune_frac must be in (0, 1]");
+    if (k < 1 || k > IVF_MAX_K_RESULTS) return fail(IVF_EINVAL, "k=%d must be in [1, %d]", k, IVF_MAX_K_RESULTS);
+    const int P = nprobe, L = ix->L, M = ix->M, D = ix->D;
+    const int64_t K = ix->K;
+    const int64_t PL = (int64_t)P * L;
+    if (PL > (1 << 20)) return fail(IVF_EINVAL, "nprobe*L=%lld exceeds 2^20", (long long)PL);
+    const int S = (int)ivf_num_kept(P, L, prune_frac);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+    // queries per pass: bounded by the distance tile
+    int64_t tile = ix->scratch_limit / (K * (int64_t)sizeof(float));
+    if (tile < 1) tile = 1;
+    if (tile > nq) tile = nq;
+    if (tile >= GT) tile -= tile % GT;
+
+    // workgroups per query in the scan: fill the chip when the batch is small
+    int nsplit = (int)((2048 + tile - 1) / tile);
+    if (nsplit > 64) nsplit = 64;
+    if (nsplit > (S + 15) / 16) nsplit = (S + 15) / 16;
+    while (nsplit > 1 && (int64_t)nsplit * SCAN_WAVES * k > 8192) --nsplit;
+    if (nsplit < 1) nsplit = 1;
+    const int n_lists = nsplit * SCAN_WAVES;
+    const int merge_n = n_lists * k, merge_pow2 = next_pow2(merge_n);
+
+    int rc;
+    if ((rc = ensure(ix->dt, (size_t)tile * K * sizeof(float)))) return rc;
+    if ((rc = ensure(ix->qn, (size_t)tile * sizeof(float)))) return rc;
+    if ((rc = ensure(ix->probe_id, (size_t)tile * P * sizeof(int32_t)))) return rc;
+    if ((rc = ensure(ix->probe_d, (size_t)tile * P * sizeof(float)))) return rc;
+    if ((rc = ensure(ix->scores, (size_t)tile * PL * sizeof(float)))) return rc;
+    if ((rc = ensure(ix->desc, (size_t)tile * S * sizeof(SubDesc)))) return rc;
+    if ((rc = ensure(ix->lut, (size_t)tile * M * 256 * sizeof(float)))) return rc;
+    if ((rc = ensure(ix->partial, (size_t)tile * merge_n * sizeof(uint64_t)))) return rc;
+
+    const size_t scan_lds = (size_t)(M * 256 + 256) * sizeof(float) +
+                            (size_t)SCAN_WAVES * pool_capacity(k) * sizeof(uint64_t);
+    const size_t merge_lds = (size_t)merge_pow2 * sizeof(uint64_t);
+    if (scan_lds > 64 * 1024) {   // above the default dynamic LDS window
+        const void *fn = M == 16 ? reinterpret_cast<const void *>(&scan_kernel<16>)
+                                 : reinterpret_cast<const void *>(&scan_kernel<8>);
+        HIPCHK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds));
+    }
+
+    for (int64_t q0 = 0; q0 < nq; q0 += tile) {
+        const int64_t n = (nq - q0 < tile) ? nq - q0 : tile;
+        const float *Q = queries + q0 * D;
+        float *Dt = static_cast<float *>(ix->dt.p);
+        float *qn = static_cast<float *>(ix->qn.p);
+        int32_t *pid = probe_id_out ? probe_id_out + q0 * P : static_cast<int32_t *>(ix->probe_id.p);
+        float *pd = probe_d_out ? probe_d_out + q0 * P : static_cast<float *>(ix->probe_d.p);
+        float *scores = static_cast<float *>(ix->scores.p);
+        SubDesc *desc = static_cast<SubDesc *>(ix->desc.p);
+        float *lut = static_cast<float *>(ix->lut.p);
+        uint64_t *partial = static_cast<uint64_t *>(ix->partial.p);
+
+        row_norm_kernel<<<dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st>>>(Q, n, D, qn);
+        LAUNCHCHK("row_norm_kernel");
+        if ((rc = launch_coarse(Q, qn, n, ix->centroids, ix->cnorm, K, D, Dt, st))) return rc;
+        if ((rc = launch_probe_select(Dt, n, K, P, pid, pd, st))) return rc;
+
+        const int64_t total = n * PL;
+        score_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
+            Dt, K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, scores, total);
+        LAUNCHCHK("score_kernel");
+
+        int64_t *ks = kept_sub_out ? kept_sub_out + q0 * S : nullptr;
+        int64_t *ns = n_scanned_out ? n_scanned_out + q0 : nullptr;
+        if (PL > 8192)
+            prune_kernel<1024><<<dim3((unsigned)n), dim3(1024), 0, st>>>(
+                scores, (int)PL, S, pid, P, L, ix->sub_offsets, ix->blk_off, desc, ks, ns);
+        else
+            prune_kernel<256><<<dim3((unsigned)n), dim3(256), 0, st>>>(
+                scores, (int)PL, S, pid, P, L, ix->sub_offsets, ix->blk_off, desc, ks, ns);
+        LAUNCHCHK("prune_kernel");
+
+        lut_kernel<<<dim3((unsigned)n), dim3(256), (size_t)D * sizeof(float), st>>>(Q, D, M, ix->codebook, lut);
+        LAUNCHCHK("lut_kernel");
+
+        if (M == 16)
+            scan_kernel<16><<<dim3((unsigned)(n * nsplit)), dim3(SCAN_BLOCK), scan_lds, st>>>(
+                ix->blocks, ix->ids, ix->const_table, desc, S, lut, k, nsplit, partial);
+        else
+            scan_kernel<8><<<dim3((unsigned)(n * nsplit)), dim3(SCAN_BLOCK), scan_lds, st>>>(
+                ix->blocks, ix->ids, ix->const_table, desc, S, lut, k, nsplit, partial);
+        LAUNCHCHK("scan_kernel");
+
+        merge_kernel<256><<<dim3((unsigned)n), dim3(256), merge_lds, st>>>(
+            partial, merge_n, merge_pow2, k, out_ids + q0 * k, out_dists + q0 * k);
+        LAUNCHCHK("merge_kernel");
+    }
+    return IVF_OK;
+}
+
+extern "C" int ivf_search(ivf_index *ix, const float *queries, int64_t nq, int nprobe, float prune_frac,
+                          int k, int32_t *out_ids, float *out_dists, void *hip_stream)
+{
+    return ivf_search_stages(ix, queries, nq, nprobe, prune_frac, k, out_ids, out_dists, nullptr,
+                             nullptr, nullptr, nullptr, hip_stream);
+}
+
+extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const float *x, int64_t nq, int P,
+                               int32_t *out_id, float *out_d, void *hip_stream)
+{
+    if (!centroids || !x || !out_id || !out_d) return fail(IVF_EINVAL, "NULL argument");
+    if (D < 4 || D % 4 || D > IVF_MAX_D) return fail(IVF_EINVAL, "D=%d must be a multiple of 4", D);
+    if (K < 1 || P < 1 || P > K) return fail(IVF_EINVAL, "need 1 <= P <= K");
+    if (nq < 0 || nq >= (1ll << 31)) return fail(IVF_EINVAL, "nq out of range");
+    if (!aligned16(centroids) || !aligned16(x)) return fail(IVF_EINVAL, "centroids and x must be 16-byte aligned");
+    if (nq == 0) return IVF_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    int64_t tile = (4ll << 30) / (K * (int64_t)sizeof(float));
+    if (tile < 1) tile = 1;
+    if (tile > nq) tile = nq;
+    if (tile >= GT) tile -= tile % GT;
+    float *cn = nullptr, *xn = nullptr, *Dt = nullptr;
+    int rc = IVF_OK;
+    auto body = [&]() -> int {
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&cn), (size_t)K * sizeof(float)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), (size_t)tile * sizeof(float)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&Dt), (size_t)tile * K * sizeof(float)));
+        row_norm_kernel<<<dim3((unsigned)((K + 3) / 4)), dim3(256), 0, st>>>(centroids, K, D, cn);
+        LAUNCHCHK("row_norm_kernel");
+        for (int64_t q0 = 0; q0 < nq; q0 += tile) {
+            const int64_t n = (nq - q0 < tile) ? nq - q0 : tile;
+            row_norm_kernel<<<dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st>>>(x + q0 * D, n, D, xn);
+            LAUNCHCHK("row_norm_kernel");
+            int r2;
+            if ((r2 = launch_coarse(x + q0 * D, xn, n, centroids, cn, K, D, Dt, st))) return r2;
+            if ((r2 = launch_probe_select(Dt, n, K, P, out_id + q0 * P, out_d + q0 * P, st))) return r2;
+        }
+        HIPCHK(hipStreamSynchronize(st));
+        return IVF_OK;
+    };
+    rc = body();
+    std::string keep = g_err;
+    (void)hipStreamSynchronize(st);
+    if (cn) (void)hipFree(cn);
+    if (xn) (void)hipFree(xn);
+    if (Dt) (void)hipFree(Dt);
+    g_err = keep;
+    return rc;
+}
+
+extern "C" int ivf_encode(const ivf_index_desc *t, const float *x, int64_t n, const int32_t *region_in,
+                          int32_t *out_region, int32_t *out_sub, uint8_t *out_codes,
+                          uint8_t *out_const_byte, float *out_const_t, void *hip_stream)
+{
+    int rc = check_trained(t);
+    if (rc) return rc;
+    if (!x || !out_region || !out_sub || !out_codes) return fail(IVF_EINVAL, "NULL argument");
+    if (t->const_table && !out_const_byte) return fail(IVF_EINVAL, "out_const_byte is NULL");
+    if (!aligned16(x)) return fail(IVF_EINVAL, "x must be 16-byte aligned");
+    if (n < 0 || n >= (1ll << 31)) return fail(IVF_EINVAL, "n out of range");
+    if (n == 0) return IVF_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (region_in) {
+        if (region_in != out_region)
+            HIPCHK(hipMemcpyAsync(out_region, region_in, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+    } else {
+        float *d1 = nullptr;
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&d1), (size_t)n * sizeof(float)));
+        rc = ivf_coarse_topk(t->centroids, t->K, t->D, x, n, 1, out_region, d1, hip_stream);
+        std::string keep = g_err;
+        (void)hipFree(d1);
+        g_err = keep;
+        if (rc) return rc;
+    }
+    encode_kernel<<<dim3((unsigned)n), dim3(64), (size_t)4 * t->D * sizeof(float), st>>>(
+        x, n, t->D, t->M, t->L, out_region, t->centroids, t->nbr, t->alpha, t->cs_dist2, t->pq_codebook,
+        t->const_table, out_sub, out_codes, out_const_byte, out_const_t);
+    LAUNCHCHK("encode_kernel");
+    HIPCHK(hipStreamSynchronize(st));
+    return IVF_OK;
+}
+
+extern "C" int ivf_alpha_stats(const float *centroids, int64_t K, int D, const int32_t *nbr, int L,
+                               const float *x, int64_t n, const int32_t *region, double *num, double *den,
+                               void *hip_stream)
+{
+    if (!centroids || !nbr || !x || !region || !num || !den) return fail(IVF_EINVAL, "NULL argument");
+    if (D < 1 || D > IVF_MAX_D || K < 1 || L < 1) return fail(IVF_EINVAL, "bad sizes");
+    if (n < 0 || n >= (1ll << 31)) return fail(IVF_EINVAL, "n out of range");
+    if (n == 0) return IVF_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    alpha_stats_kernel<<<dim3((unsigned)n), dim3(64), (size_t)D * sizeof(float), st>>>(
+        x, n, D, L, region, centroids, nbr, num, den);
+    LAUNCHCHK("alpha_stats_kernel");
+    return IVF_OK;
+}

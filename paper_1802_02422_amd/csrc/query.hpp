@@ -1,0 +1,94 @@
+// Stages 2-4 of the query path: subcentroid scoring by the closed form of
+// Eq. (7), pruning to the S closest subregions, and the per-query table of
+// -2<q_m, r^m_j> of Eq. (6).
+#pragma once
+#include "select.hpp"
+
+namespace ivf {
+
+// One kept subregion of one query, as the scan consumes it.
+struct SubDesc {
+    uint32_t blk;    // start of the subregion's record block, in 64-byte units
+    uint32_t pos0;   // grouped position of its first point (indexes ids[])
+    uint32_t len;    // number of points
+    float base;      // distance from the query to the subcentroid
+};
+
+// score[q][p][l] = (1-a) D[q][r] + a D[q][nbr[r][l]] + cst[r][l], r = probe_id[q][p],
+// cst[r][l] = -a(1-a)||c_r - s_l||^2 tabulated at load time.  The neighbour
+// distances are gathered from the stage-1 distance tile, not recomputed.
+__global__ __launch_bounds__(256) void score_kernel(
+    const float *__restrict__ Dt, int64_t K, const int32_t *__restrict__ probe_id,
+    const float *__restrict__ probe_d, int P, int L, const int32_t *__restrict__ nbr,
+    const float *__restrict__ cst, const float *__restrict__ alpha, float *__restrict__ scores,
+    int64_t total)
+{
+    int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    int l = (int)(idx % L);
+    int64_t qp = idx / L;
+    int64_t q = qp / P;
+    int64_t r = probe_id[qp];
+    float a = alpha[r];
+    float dr = probe_d[qp];
+    float ds = Dt[q * K + nbr[r * L + l]];
+    scores[idx] = fmaf(a, ds, fmaf(1.f - a, dr, cst[r * L + l]));
+}
+
+// Keep the S smallest of the P*L scores of each query by (score, r*L + l).
+// probe_id is ascending in r, so position order in the score row is
+// subregion-id order and the descriptors come out sorted by address.
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void prune_kernel(
+    const float *__restrict__ scores, int PL, int S, const int32_t *__restrict__ probe_id, int P,
+    int L, const uint32_t *__restrict__ sub_offsets, const uint32_t *__restrict__ blk_off,
+    SubDesc *__restrict__ desc, int64_t *__restrict__ kept_sub, int64_t *__restrict__ n_scanned)
+{
+    __shared__ SelectShared sh;
+    __shared__ unsigned long long codes_total;
+    const int64_t q = blockIdx.x;
+    const float *row = scores + q * PL;
+    if (threadIdx.x == 0) codes_total = 0;
+    auto key = [row](int64_t i) { return float_key(row[i]); };
+    uint32_t pivot, need;
+    block_radix_select<BLOCK>(key, PL, (uint32_t)S, sh, pivot, need);
+    unsigned long long mine = 0;
+    block_emit_selected<BLOCK>(key, PL, (uint32_t)S, pivot, need, sh,
+                               [&](uint32_t pos, int64_t i, uint32_t k) {
+                                   int64_t r = probe_id[q * P + i / L];
+                                   int64_t b = r * L + (i % L);
+                                   uint32_t p0 = sub_offsets[b], p1 = sub_offsets[b + 1];
+                                   SubDesc d;
+                                   d.blk = blk_off[b];
+                                   d.pos0 = p0;
+                                   d.len = p1 - p0;
+                                   d.base = key_float(k);
+                                   desc[q * S + pos] = d;
+                                   if (kept_sub) kept_sub[q * S + pos] = b;
+                                   mine += d.len;
+                               });
+    if (mine) atomicAdd(&codes_total, mine);
+    __syncthreads();
+    if (threadIdx.x == 0 && n_scanned) n_scanned[q] = (int64_t)codes_total;
+}
+
+// T[q][m][j] = -2 <q_m, r^m_j>; one workgroup of 256 threads per query,
+// thread j owns codeword j of every sub-quantiser.
+__global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ Q, int D, int M,
+                                                  const float *__restrict__ codebook,
+                                                  float *__restrict__ T)
+{
+    extern __shared__ float qs[];
+    const int64_t q = blockIdx.x;
+    const int j = threadIdx.x, ds = D / M;
+    for (int i = j; i < D; i += 256) qs[i] = Q[q * D + i];
+    __syncthreads();
+    for (int m = 0; m < M; ++m) {
+        const float *cw = codebook + ((int64_t)m * 256 + j) * ds;
+        float s = 0.f;
+        for (int i = 0; i < ds; ++i) s = fmaf(qs[m * ds + i], cw[i], s);
+        T[(q * M + m) * 256 + j] = -2.f * s;
+    }
+}
+
+}  // namespace ivf

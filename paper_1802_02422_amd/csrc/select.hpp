@@ -1,0 +1,123 @@
+// Exact selection of the nsel smallest of n items by (key, position) inside
+// one workgroup: an MSB-first radix select on order-preserving uint32 keys
+// followed by an ordered compaction, so the winners come out in ascending
+// position and ties on the key resolve to the lowest positions.
+#pragma once
+#include "util.hpp"
+
+namespace ivf {
+
+struct SelectShared {
+    uint32_t hist[256];
+    uint32_t scan[16];
+    uint32_t pick[2];
+};
+
+// Finds the key value `pivot` of the nsel-th smallest item and the number
+// `need` of items equal to pivot that belong to the selection (those at the
+// lowest positions).  key(i) must be pure.  1 <= nsel <= n.
+template <int BLOCK, class KeyFn>
+__device__ void block_radix_select(KeyFn key, int64_t n, uint32_t nsel, SelectShared &sh,
+                                   uint32_t &pivot, uint32_t &need)
+{
+    const int tid = threadIdx.x;
+    uint32_t prefix = 0, mask = 0, remaining = nsel;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        for (int i = tid; i < 256; i += BLOCK) sh.hist[i] = 0;
+        __syncthreads();
+        for (int64_t i = tid; i < n; i += BLOCK) {
+            uint32_t k = key(i);
+            if ((k & mask) == prefix) atomicAdd(&sh.hist[(k >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid < WAVE) {
+            uint32_t c[4], s = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { c[j] = sh.hist[4 * tid + j]; s += c[j]; }
+            uint32_t inc = wave_inclusive_scan(s);
+            uint32_t exc = inc - s;
+            if (exc < remaining && inc >= remaining) {   // exactly one lane
+                uint32_t cum = exc;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (cum < remaining && cum + c[j] >= remaining) {
+                        sh.pick[0] = 4 * tid + j;
+                        sh.pick[1] = remaining - cum;
+                    }
+                    cum += c[j];
+                }
+            }
+        }
+        __syncthreads();
+        prefix |= sh.pick[0] << shift;
+        mask |= 0xFFu << shift;
+        remaining = sh.pick[1];
+        __syncthreads();
+    }
+    pivot = prefix;
+    need = remaining;
+}
+
+// Calls emit(out_pos, i, key) for every selected item i, where out_pos is the
+// item's rank among the selected ones in ascending i.
+template <int BLOCK, class KeyFn, class EmitFn>
+__device__ void block_emit_selected(KeyFn key, int64_t n, uint32_t nsel, uint32_t pivot,
+                                    uint32_t need, SelectShared &sh, EmitFn emit)
+{
+    const int tid = threadIdx.x;
+    uint32_t run_lt = 0, run_eq = 0;
+    for (int64_t base = 0; base < n; base += BLOCK) {
+        int64_t i = base + tid;
+        bool valid = i < n;
+        uint32_t k = valid ? key(i) : 0u;
+        bool lt = valid && k < pivot, eq = valid && k == pivot;
+        uint32_t packed = (lt ? 1u : 0u) | (eq ? 0x10000u : 0u), total;
+        uint32_t exc = block_exclusive_scan<BLOCK>(packed, sh.scan, total);
+        uint32_t lt_ex = exc & 0xFFFFu, eq_ex = run_eq + (exc >> 16);
+        if (lt) {
+            emit(run_lt + lt_ex + (eq_ex < need ? eq_ex : need), i, k);
+        } else if (eq && eq_ex < need) {
+            emit(run_lt + lt_ex + eq_ex, i, k);
+        }
+        run_lt += total & 0xFFFFu;
+        run_eq += total >> 16;
+        if (run_lt + (run_eq < need ? run_eq : need) >= nsel) break;   // uniform
+    }
+}
+
+// In-place ascending bitonic sort of n (a power of two) uint64 keys in LDS by
+// the whole workgroup.
+template <int BLOCK>
+__device__ void block_bitonic_sort(uint64_t *a, int n)
+{
+    for (int size = 2; size <= n; size <<= 1)
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            __syncthreads();
+            for (int t = threadIdx.x; t < n / 2; t += BLOCK) {
+                int i = 2 * t - (t & (stride - 1)), j = i + stride;
+                bool up = (i & size) == 0;
+                uint64_t x = a[i], y = a[j];
+                if ((x > y) == up) { a[i] = y; a[j] = x; }
+            }
+        }
+    __syncthreads();
+}
+
+// The same for one wavefront on its private LDS array.
+__device__ __forceinline__ void wave_bitonic_sort(uint64_t *a, int n)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+    for (int size = 2; size <= n; size <<= 1)
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            wave_sync();
+            for (int t = lane; t < n / 2; t += WAVE) {
+                int i = 2 * t - (t & (stride - 1)), j = i + stride;
+                bool up = (i & size) == 0;
+                uint64_t x = a[i], y = a[j];
+                if ((x > y) == up) { a[i] = y; a[j] = x; }
+            }
+        }
+    wave_sync();
+}
+
+}  // namespace ivf

@@ -1,0 +1,111 @@
+// Small device helpers shared by the kernels: order-preserving float keys,
+// wavefront (64 lanes) and workgroup scans / reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ivf {
+
+constexpr int WAVE = 64;
+constexpr uint64_t EMPTY_KEY = ~0ull;
+
+// fp32 -> uint32 such that a < b  <=>  key(a) < key(b) (for non-NaN values)
+__device__ __forceinline__ uint32_t float_key(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    return u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+
+__device__ __forceinline__ float key_float(uint32_t k)
+{
+    uint32_t u = k ^ ((k >> 31) ? 0x80000000u : 0xFFFFFFFFu);
+    return __uint_as_float(u);
+}
+
+// (distance, id) packed so that integer order is (distance, id) order
+__device__ __forceinline__ uint64_t dist_id_key(float d, int32_t id)
+{
+    return ((uint64_t)float_key(d) << 32) | (uint32_t)id;
+}
+
+// LDS traffic between lanes of one wavefront: keep the compiler from moving
+// LDS accesses across this point (the hardware executes a wave's LDS
+// instructions in order).
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+#pragma unroll
+    for (int o = 1; o < WAVE; o <<= 1) {
+        uint32_t t = __shfl_up(v, o, WAVE);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+
+// argmin over the wave of (value, index) pairs, lowest index on equal values;
+// every lane receives the winner.
+__device__ __forceinline__ void wave_argmin(float &v, int &idx)
+{
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) {
+        float ov = __shfl_xor(v, o, WAVE);
+        int oi = __shfl_xor(idx, o, WAVE);
+        if (ov < v || (ov == v && oi < idx)) { v = ov; idx = oi; }
+    }
+}
+
+__device__ __forceinline__ void wave_argmin(double &v, int &idx)
+{
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) {
+        double ov = __shfl_xor(v, o, WAVE);
+        int oi = __shfl_xor(idx, o, WAVE);
+        if (ov < v || (ov == v && oi < idx)) { v = ov; idx = oi; }
+    }
+}
+
+// Exclusive scan of one uint32 per thread over a workgroup of BLOCK threads
+// (BLOCK a multiple of 64).  sh must hold BLOCK/64 words of LDS.  Returns the
+// exclusive prefix; total receives the workgroup sum.  Contains barriers.
+template <int BLOCK>
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *sh, uint32_t &total)
+{
+    constexpr int NW = BLOCK / WAVE;
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    uint32_t inc = wave_inclusive_scan(v);
+    if (lane == WAVE - 1) sh[w] = inc;
+    __syncthreads();
+    uint32_t before = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        uint32_t s = sh[i];
+        if (i < w) before += s;
+        tot += s;
+    }
+    __syncthreads();
+    total = tot;
+    return before + inc - v;
+}
+
+}  // namespace ivf

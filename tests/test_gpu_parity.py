@@ -1,0 +1,166 @@
+"""HIP library vs oracle through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_1802_02422_amd as ivf
+from oracle import ivf_oracle as orc
+import parity
+
+
+@pytest.fixture(scope="module")
+def tiny_gpu(tiny):
+    spec, ix, Q, X = tiny
+    handle = ivf.ivf_load_index(parity.to_device(ix))
+    return spec, ix, Q, X, handle
+
+
+def test_library_is_loaded():
+    assert ivf.load_library() is not None and torch.cuda.is_available()
+
+
+def test_coarse_topk_matches_bruteforce(tiny):
+    spec, ix, Q, X = tiny
+    print("case: coarse_topk tiny", flush=True)
+    C = torch.from_numpy(ix.centroids).cuda()
+    for nq, P in ((100, 16), (1, 1), (77, 1), (100, 1024)):
+        gid, gd = ivf.ivf_coarse_topk(C, torch.from_numpy(Q[:nq]).cuda(), P)
+        gid, gd = gid.cpu().numpy(), gd.cpu().numpy()
+        oid, od = orc.probe(Q[:nq], ix.centroids, P)
+        at = parity.abs_term(ix, Q[:nq])
+        c64 = ix.centroids.astype(np.float64)
+        near = 0
+        for q in range(nq):
+            dist = lambda j: float(((Q[q].astype(np.float64) - c64[j]) ** 2).sum())
+            kind, gap = parity.compare_selection(gid[q], oid[q], dist, od[q, -1], max(1e-5 * od[q, -1], at[q]))
+            assert kind != "mismatch", (nq, P, q, gap)
+            near += kind == "near"
+        assert near <= 2
+        d_true = ((Q[:nq].astype(np.float64)[:, None] - c64[gid]) ** 2).sum(-1)
+        assert (np.abs(gd - d_true) <= np.maximum(1e-4 * d_true, at[:, None])).all()
+
+
+def test_search_tiny_all_stages(tiny_gpu):
+    spec, ix, Q, X, handle = tiny_gpu
+    print("case: search tiny", spec, flush=True)
+    out = parity.run_gpu_search(handle, Q, spec.nprobe, spec.prune_frac, spec.k)
+    rep = parity.check_search(ix, Q, spec.nprobe, spec.prune_frac, spec.k, out)
+    print(rep)
+    rep.assert_ok()
+
+
+@pytest.mark.parametrize("nprobe,tau,k,nq", [(1, 1.0, 1, 5), (16, 0.5, 10, 1), (64, 0.25, 100, 33),
+                                             (1024, 1.0, 20, 3), (7, 0.01, 1024, 4), (3, 0.3, 100, 100)])
+def test_search_tiny_parameter_corners(tiny_gpu, nprobe, tau, k, nq):
+    spec, ix, Q, X, handle = tiny_gpu
+    print("case: corners", nprobe, tau, k, nq, flush=True)
+    out = parity.run_gpu_search(handle, Q[:nq], nprobe, tau, k)
+    rep = parity.check_search(ix, Q[:nq], nprobe, tau, k, out)
+    print(rep)
+    rep.assert_ok(max_near_frac=0.2)
+
+
+def test_search_is_deterministic_and_matches_plain_entry(tiny_gpu):
+    spec, ix, Q, X, handle = tiny_gpu
+    Qd = torch.from_numpy(Q).cuda()
+    a = ivf.ivf_search_stages(handle, Qd, spec.nprobe, spec.prune_frac, spec.k)
+    ids, d = ivf.ivf_search(handle, Qd, spec.nprobe, spec.prune_frac, spec.k)
+    b = ivf.ivf_search_stages(handle, Qd, spec.nprobe, spec.prune_frac, spec.k)
+    torch.cuda.synchronize()
+    for n in a:
+        assert torch.equal(a[n], b[n]), n
+    assert torch.equal(ids, a["ids"]) and torch.equal(d, a["dists"])
+
+
+def test_query_tiling_gives_identical_results(tiny_gpu):
+    spec, ix, Q, X, handle = tiny_gpu
+    Qd = torch.from_numpy(Q).cuda()
+    a = ivf.ivf_search_stages(handle, Qd, spec.nprobe, spec.prune_frac, spec.k)
+    h2 = ivf.ivf_load_index(parity.to_device(ix))
+    ivf.ivf_set_scratch_limit(h2, 37 * ix.K * 4)          # distance tile of 37 queries: 3 passes, ragged tail
+    b = ivf.ivf_search_stages(h2, Qd, spec.nprobe, spec.prune_frac, spec.k)
+    torch.cuda.synchronize()
+    for n in a:
+        assert torch.equal(a[n], b[n]), n
+
+
+def test_empty_and_invalid_arguments(tiny_gpu):
+    spec, ix, Q, X, handle = tiny_gpu
+    Qd = torch.from_numpy(Q).cuda()
+    ids, d = ivf.ivf_search(handle, Qd[:0], 4, 0.5, 3)
+    assert ids.shape == (0, 3)
+    for bad in (dict(nprobe=0), dict(nprobe=ix.K + 1), dict(prune_frac=0.0), dict(prune_frac=1.5),
+                dict(k=0), dict(k=5000)):
+        args = dict(nprobe=4, prune_frac=0.5, k=3)
+        args.update(bad)
+        with pytest.raises(ivf.IvfError):
+            ivf.ivf_search(handle, Qd, args["nprobe"], args["prune_frac"], args["k"])
+    assert "must be" in ivf.ivf_last_error()
+
+
+def test_encode_matches_oracle(tiny):
+    spec, ix, Q, X = tiny
+    print("case: encode tiny", flush=True)
+    n = 5000
+    x = X[:n]
+    desc = parity.to_device(ix, with_codes=False)
+    region, sub, codes, byte, t = ivf.ivf_encode(desc, torch.from_numpy(x).cuda(), want_t=True)
+    region, sub, codes, byte, t = (v.cpu().numpy() for v in (region, sub, codes, byte, t))
+    enc = orc.encode(x, ix.centroids, ix.nbr, ix.alpha, ix.pq_codebook, ix.const_table)
+    assert (region == enc.region).mean() >= 0.999
+    same = (region == enc.region) & (sub == enc.sub)
+    assert same.mean() >= 0.995, same.mean()
+    code_same = (codes[same] == enc.codes[same])
+    assert code_same.mean() >= 0.999, code_same.mean()
+    full = same & (codes == enc.codes).all(1)
+    np.testing.assert_allclose(t[full], enc.t[full], rtol=1e-4, atol=2e-6)
+    assert (byte[full] == enc.const_byte[full]).mean() >= 0.99
+    # every disagreement must be a near-tie of the oracle's own fp64 decision
+    c64 = ix.centroids.astype(np.float64)
+    for i in np.flatnonzero(region != enc.region):
+        d = ((x[i].astype(np.float64) - c64[[region[i], enc.region[i]]]) ** 2).sum(1)
+        assert abs(d[0] - d[1]) <= 1e-5 * d[1]
+    for i in np.flatnonzero((region == enc.region) & (sub != enc.sub)):
+        r = region[i]
+        mus = c64[r][None] + float(ix.alpha[r]) * (c64[ix.nbr[r]] - c64[r][None])
+        d = ((x[i].astype(np.float64)[None] - mus) ** 2).sum(1)
+        assert abs(d[sub[i]] - d[enc.sub[i]]) <= 1e-5 * max(d[enc.sub[i]], 1.0)
+    ds = ix.D // ix.M
+    for i in np.flatnonzero(same & ~(codes == enc.codes).all(1)):
+        e = x[i].astype(np.float64) - enc.mu[i]
+        for m in np.flatnonzero(codes[i] != enc.codes[i]):
+            dd = ((e[m * ds:(m + 1) * ds][None] - ix.pq_codebook[m].astype(np.float64)) ** 2).sum(1)
+            assert abs(dd[codes[i, m]] - dd[enc.codes[i, m]]) <= 1e-5 * max(dd[enc.codes[i, m]], 1e-3)
+    tab = ix.const_table.astype(np.float64)
+    for i in np.flatnonzero(full & (byte != enc.const_byte)):
+        assert abs(abs(tab[byte[i]] - enc.t[i]) - abs(tab[enc.const_byte[i]] - enc.t[i])) <= 4e-6
+
+
+def test_encode_with_given_regions(tiny):
+    spec, ix, Q, X = tiny
+    n = 1000
+    desc = parity.to_device(ix, with_codes=False)
+    xd = torch.from_numpy(X[:n]).cuda()
+    r1, s1, c1, b1, _ = ivf.ivf_encode(desc, xd)
+    r2, s2, c2, b2, _ = ivf.ivf_encode(desc, xd, region_in=r1)
+    assert torch.equal(r1, r2) and torch.equal(s1, s2) and torch.equal(c1, c2) and torch.equal(b1, b2)
+
+
+def test_alpha_stats_match_oracle(tiny):
+    spec, ix, Q, X = tiny
+    n = 20000
+    x = X[:n]
+    reg, _ = orc.assign(x, ix.centroids)
+    dev = torch.device("cuda:0")
+    num = torch.zeros(ix.K, dtype=torch.float64, device=dev)
+    den = torch.zeros(ix.K, dtype=torch.float64, device=dev)
+    ivf.ivf_alpha_stats(torch.from_numpy(ix.centroids).to(dev), torch.from_numpy(ix.nbr).to(dev),
+                        torch.from_numpy(x).to(dev), torch.from_numpy(reg).to(dev), num, den)
+    torch.cuda.synchronize()
+    num, den = num.cpu().numpy(), den.cpu().numpy()
+    ref = orc.learn_alpha(x, reg, ix.centroids, ix.nbr)
+    has = den > 0
+    a = np.clip(num[has] / den[has], 0, 1)
+    np.testing.assert_allclose(a, ref[has], rtol=0, atol=2e-6)
