@@ -1,0 +1,153 @@
+#!/usr/bin/env python3
+"""Throughput of the batched query path on one MI355X.
+
+A "step" is one pass of the whole path (coarse distances + top-nprobe, subcentroid
+scoring, pruning, lookup tables, ADC scan, k-select) over the workload's full
+query batch, with queries and index resident in HBM when the timed region
+starts.  Prints one JSON line with queries/s, the roofline of the dominant
+kernel (the ADC scan, timed with HIP events on its own stream inside the
+library) and the CPU oracle timed on the host cores on a bounded sample of the
+same queries.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+DESC_BYTES = 16          # one kept-subregion descriptor read by the scan
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def download_index(desc, spec):
+    """Flat device index -> the oracle's Index of numpy arrays (host)."""
+    import numpy as np
+    from oracle import ivf_oracle as orc
+    h = lambda t: t.cpu().numpy()
+    return orc.Index(spec.D, spec.M, spec.L, spec.K, spec.N, h(desc.centroids), h(desc.nbr), h(desc.alpha),
+                     h(desc.cs_dist2), h(desc.pq_codebook), h(desc.const_table),
+                     h(desc.sub_offsets).view(np.uint32), h(desc.codes), h(desc.const_byte), h(desc.ids))
+
+
+def cpu_baseline(ix, Q, spec, budget_s=20.0):
+    """The oracle's whole-path search on the host cores, on as many of the same queries as fit the budget."""
+    import numpy as np
+    from oracle import ivf_oracle as orc
+    cores = len(os.sched_getaffinity(0))
+    omp = int(os.environ.get("OMP_NUM_THREADS", cores))
+    cores = min(cores, omp)
+    tau = float(np.float32(spec.prune_frac))
+    n0 = min(Q.shape[0], max(2, cores))
+    t = time.time()
+    orc.search(ix, Q[:n0], spec.nprobe, tau, spec.k)
+    per_q = (time.time() - t) / n0
+    n = int(min(Q.shape[0], max(n0, budget_s / max(per_q, 1e-9))))
+    t = time.time()
+    _, _, ns = orc.search(ix, Q[:n], spec.nprobe, tau, spec.k)
+    dt = time.time() - t
+    return {"value": n / dt, "unit": "queries/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {n} of {Q.shape[0]} queries of the same workload, full index, {dt:.1f} s wall",
+            "codes_per_s": float(ns.sum()) / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=os.environ.get("IVF_BENCH_WORKLOAD", "deep1b"))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--scratch-gib", type=float, default=48.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synthdata as sd
+    import paper_1802_02422_amd as ivf
+    from paper_1802_02422_amd import index_builder
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = torch.device("cuda:0")
+    spec = sd.WORKLOADS[args.workload]
+    ivf.load_library()
+
+    t0 = time.time()
+    mix = sd.make_mixture(spec.kind, spec.n_mix, spec.D, dev)
+    mode = "mixture" if spec.K >= (1 << 18) else "kmeans"
+    desc, stats = index_builder.build(spec, mix, mode=mode, log=log)
+    Q = sd.draw_queries(mix, spec.nq).contiguous()
+    log(f"index built in {time.time() - t0:.1f}s ({mode}); stats {stats}")
+
+    host_ix = None
+    if not args.no_cpu_baseline:
+        host_ix = download_index(desc, spec)
+        log(f"index downloaded to host {time.time() - t0:.1f}s")
+    handle = ivf.ivf_load_index(desc)
+    desc.codes = desc.const_byte = desc.ids = None      # the handle owns its own copy
+    torch.cuda.empty_cache()
+    ivf.ivf_set_scratch_limit(handle, int(args.scratch_gib * (1 << 30)))
+    log(f"index loaded {time.time() - t0:.1f}s")
+
+    out_ids = torch.empty((spec.nq, spec.k), dtype=torch.int32, device=dev)
+    out_d = torch.empty((spec.nq, spec.k), dtype=torch.float32, device=dev)
+    st = ivf.ivf_search_stages(handle, Q, spec.nprobe, spec.prune_frac, spec.k)
+    torch.cuda.synchronize()
+    codes_scanned = int(st["n_scanned"].sum().item())
+    S = ivf.ivf_num_kept(spec.nprobe, spec.L, spec.prune_frac)
+    del st
+
+    for _ in range(args.warmup):
+        ivf.ivf_search(handle, Q, spec.nprobe, spec.prune_frac, spec.k, out_ids, out_d)
+    torch.cuda.synchronize()
+    ivf.ivf_profile_enable(handle, True)
+    ivf.ivf_profile_read(handle)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        ivf.ivf_search(handle, Q, spec.nprobe, spec.prune_frac, spec.k, out_ids, out_d)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    stage_ms, passes = ivf.ivf_profile_read(handle)
+    ivf.ivf_profile_enable(handle, False)
+
+    ms_per_step = (t2 - t1) * 1e3 / args.steps
+    qps = spec.nq / (ms_per_step * 1e-3)
+    scan_launches = passes                      # one scan launch per pass over a tile of queries
+    scan_ms = stage_ms["scan"] / max(scan_launches, 1)
+    algo_bytes = (codes_scanned * (spec.M + 1) + spec.nq * S * DESC_BYTES) * args.steps / max(scan_launches, 1)
+    achieved = algo_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
+    coarse_tflops = 2.0 * spec.nq * spec.K * spec.D * args.steps / (stage_ms["coarse_gemm"] * 1e-3) / 1e12
+
+    result = {
+        "metric": "queries/s at fixed nprobe/prune budget; ADC codes scanned/s (HBM GB/s)",
+        "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": spec.name, "N": spec.N, "D": spec.D, "K": spec.K, "L": spec.L, "M": spec.M,
+                   "nq": spec.nq, "nprobe": spec.nprobe, "prune_frac": spec.prune_frac, "k": spec.k,
+                   "kept_subregions": S, "codes_scanned_per_query": codes_scanned / spec.nq,
+                   "index_build": mode, **{k_: v for k_, v in stats.items()}},
+        "codes_scanned_per_s": codes_scanned * args.steps / (stage_ms["scan"] * 1e-3) if stage_ms["scan"] > 0 else 0.0,
+        "stage_ms_per_step": {k_: v / args.steps for k_, v in stage_ms.items()},
+        "coarse_gemm_tflops": coarse_tflops,
+        "roofline": {"kernel": "scan_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "launches": scan_launches, "avg_launch_ms": scan_ms, "algorithmic_bytes_per_launch": algo_bytes},
+    }
+    if host_ix is not None:
+        result["cpu_baseline"] = cpu_baseline(host_ix, Q.cpu().numpy(), spec)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -148,14 +148,16 @@ int ivf_coarse_topk(const float *centroids, int64_t K, int D, const float *x, in
  * displacement (Section 2), the per-point term t = 2<mu, r> + ||r||^2 of
  * Eq. (6) and its nearest entry in const_table (lower index on ties).
  * Only the trained fields of `trained` are read (centroids, nbr, alpha,
- * cs_dist2, pq_codebook, const_table; const_table may be NULL, then
- * out_const_byte is not written).  Outputs: out_region [n] int32, out_sub [n]
- * int32, out_codes [n][M], out_const_byte [n], out_const_t [n] fp32 (may be
- * NULL).  Waits for the stream.
+ * cs_dist2, pq_codebook, const_table).  const_table may be NULL, then
+ * out_const_byte is not written; pq_codebook may be NULL too (index trained up
+ * to alpha only), then only region, subregion and displacement are produced.
+ * Outputs: out_region [n] int32, out_sub [n] int32, out_codes [n][M],
+ * out_const_byte [n], out_const_t [n] fp32 (may be NULL), out_residual [n][D]
+ * fp32 displacement x - mu (may be NULL).  Waits for the stream.
  */
 int ivf_encode(const ivf_index_desc *trained, const float *x, int64_t n, const int32_t *region_in,
                int32_t *out_region, int32_t *out_sub, uint8_t *out_codes, uint8_t *out_const_byte,
-               float *out_const_t, void *hip_stream);
+               float *out_const_t, float *out_residual, void *hip_stream);
 
 /*
  * Training statistics for alpha (Section 3.2, Eqs. (11)-(12)): for each of the
@@ -169,6 +171,20 @@ int ivf_encode(const ivf_index_desc *trained, const float *x, int64_t n, const i
 int ivf_alpha_stats(const float *centroids, int64_t K, int D, const int32_t *nbr, int L,
                     const float *x, int64_t n, const int32_t *region, double *num, double *den,
                     void *hip_stream);
+
+/*
+ * Per-stage device timing of ivf_search / ivf_search_stages on a handle.  While
+ * enabled, every pass over a tile of queries records HIP events on the caller's
+ * stream around its seven kernel groups, in launch order:
+ *   0 query norms + coarse distance GEMM   1 nprobe selection   2 Eq. (7) scoring
+ *   3 pruning select   4 lookup tables   5 ADC scan   6 final k-select
+ * ivf_profile_read waits for the device, writes the summed milliseconds per
+ * group to stage_ms[IVF_N_STAGES] (host) and the number of passes to *launches
+ * (host), and resets the counters.
+ */
+#define IVF_N_STAGES 7
+int ivf_profile_enable(ivf_index *index, int on);
+int ivf_profile_read(ivf_index *index, double *stage_ms, int64_t *launches);
 
 /* Message of the last error on this host thread ("" if none). */
 const char *ivf_last_error(void);

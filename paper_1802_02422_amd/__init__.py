@@ -20,4 +20,7 @@ from .binding import (  # noqa: F401
     ivf_encode,
     ivf_alpha_stats,
     ivf_last_error,
+    ivf_profile_enable,
+    ivf_profile_read,
+    STAGE_NAMES,
 )

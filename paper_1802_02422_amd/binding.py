@@ -54,8 +54,10 @@ def load_library():
     lib.ivf_num_kept.argtypes = [i32, i32, f32]
     lib.ivf_num_kept.restype = i64
     lib.ivf_coarse_topk.argtypes = [vp, i64, i32, vp, i64, i32, vp, vp, vp]
-    lib.ivf_encode.argtypes = [C.POINTER(_Desc), vp, i64, vp, vp, vp, vp, vp, vp, vp]
+    lib.ivf_encode.argtypes = [C.POINTER(_Desc), vp, i64, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.ivf_alpha_stats.argtypes = [vp, i64, i32, vp, i32, vp, i64, vp, vp, vp, vp]
+    lib.ivf_profile_enable.argtypes = [vp, i32]
+    lib.ivf_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.ivf_last_error.restype = C.c_char_p
     _lib = lib
     return lib
@@ -97,7 +99,8 @@ class IndexDesc:
     nbr: torch.Tensor                            # [K, L] int32
     alpha: torch.Tensor                          # [K] fp32
     cs_dist2: torch.Tensor                       # [K, L] fp32
-    pq_codebook: torch.Tensor                    # [M, 256, D/M] fp32
+    pq_codebook: Optional[torch.Tensor] = None   # [M, 256, D/M] fp32
+    M: int = 0                                   # only needed while pq_codebook is None
     const_table: Optional[torch.Tensor] = None   # [256] fp32
     sub_offsets: Optional[torch.Tensor] = None   # [K*L+1] uint32 bit patterns (int32 / int64 accepted)
     codes: Optional[torch.Tensor] = None         # [N, M] uint8
@@ -107,7 +110,7 @@ class IndexDesc:
     def _c(self) -> _Desc:
         K, D = self.centroids.shape
         L = self.nbr.shape[1]
-        M = self.pq_codebook.shape[0]
+        M = self.pq_codebook.shape[0] if self.pq_codebook is not None else (self.M or 8)
         _dev(self.centroids, torch.float32, "centroids")
         _dev(self.nbr, torch.int32, "nbr", (K, L))
         _dev(self.alpha, torch.float32, "alpha", (K,))
@@ -214,8 +217,8 @@ def ivf_coarse_topk(centroids: torch.Tensor, x: torch.Tensor, P: int):
 
 
 def ivf_encode(trained: IndexDesc, x: torch.Tensor, region_in: Optional[torch.Tensor] = None,
-               want_t: bool = False):
-    """(region, sub, codes, const_byte, t) for the points x [n, D]."""
+               want_t: bool = False, want_residual: bool = False):
+    """(region, sub, codes, const_byte, t[, residual]) for the points x [n, D]."""
     n = x.shape[0]
     c = trained._c()
     _dev(x, torch.float32, "x", (n, c.D))
@@ -223,11 +226,15 @@ def ivf_encode(trained: IndexDesc, x: torch.Tensor, region_in: Optional[torch.Te
     dev = x.device
     region = torch.empty(n, dtype=torch.int32, device=dev)
     sub = torch.empty(n, dtype=torch.int32, device=dev)
-    codes = torch.empty((n, c.M), dtype=torch.uint8, device=dev)
-    byte = torch.empty(n, dtype=torch.uint8, device=dev) if trained.const_table is not None else None
-    t = torch.empty(n, dtype=torch.float32, device=dev) if want_t else None
+    has_pq = trained.pq_codebook is not None
+    codes = torch.empty((n, c.M), dtype=torch.uint8, device=dev) if has_pq else None
+    byte = torch.empty(n, dtype=torch.uint8, device=dev) if has_pq and trained.const_table is not None else None
+    t = torch.empty(n, dtype=torch.float32, device=dev) if want_t and has_pq else None
+    res = torch.empty((n, c.D), dtype=torch.float32, device=dev) if want_residual else None
     _check(load_library().ivf_encode(C.byref(c), _ptr(x), n, _ptr(region_in), _ptr(region), _ptr(sub),
-                                     _ptr(codes), _ptr(byte), _ptr(t), _stream()))
+                                     _ptr(codes), _ptr(byte), _ptr(t), _ptr(res), _stream()))
+    if want_residual:
+        return region, sub, codes, byte, t, res
     return region, sub, codes, byte, t
 
 
@@ -245,3 +252,18 @@ def ivf_alpha_stats(centroids: torch.Tensor, nbr: torch.Tensor, x: torch.Tensor,
     _dev(den, torch.float64, "den", (K,))
     _check(load_library().ivf_alpha_stats(_ptr(centroids), K, D, _ptr(nbr), L, _ptr(x), n, _ptr(region),
                                           _ptr(num), _ptr(den), _stream()))
+
+
+STAGE_NAMES = ("coarse_gemm", "probe_select", "score", "prune", "lut", "scan", "merge")
+
+
+def ivf_profile_enable(index: IndexHandle, on: bool) -> None:
+    _check(load_library().ivf_profile_enable(index.ptr, 1 if on else 0))
+
+
+def ivf_profile_read(index: IndexHandle):
+    """({stage name: summed milliseconds}, number of query-tile passes) since the last read."""
+    ms = (C.c_double * len(STAGE_NAMES))()
+    n = C.c_int64()
+    _check(load_library().ivf_profile_read(index.ptr, ms, C.byref(n)))
+    return dict(zip(STAGE_NAMES, list(ms))), n.value

@@ -28,27 +28,19 @@ constexpr int GT = 128;        // tile: GT queries x GT centroids per workgroup
 constexpr int GKC = 32;        // dimensions staged per step
 constexpr int GLD = GKC + 4;   // LDS row stride in floats (keeps 16-byte alignment, spreads banks)
 
-// Dt[q][j] = max(0, qn[q] + cn[j] - 2 <Q[q], C[j]>) for one 128x128 tile per
-// workgroup of 4 wavefronts; each wavefront owns a 64x64 quadrant as 2x2
-// v_mfma_f32_32x32x2f32 accumulators.  Within a 32-dim stage lane half h
-// feeds dims [16h, 16h+16) to both operands, so one ds_read_b128 serves four
-// MFMA steps (the order of the k-summation is free).
-// Tiles are numbered centroid-tile-major so that the query tiles (small, L2
-// resident) are swept against one centroid tile after the other.
-__global__ __launch_bounds__(256) void coarse_gemm_kernel(
-    const float *__restrict__ Q, const float *__restrict__ qn, int64_t nq,
-    const float *__restrict__ C, const float *__restrict__ cn, int64_t K, int D,
-    float *__restrict__ Dt, int tiles_q)
+// One 128x128 tile of <Q[q], C[j]> per workgroup of 4 wavefronts; each
+// wavefront owns a 64x64 quadrant as 2x2 v_mfma_f32_32x32x2f32 accumulators.
+// Within a 32-dim stage lane half h feeds dims [16h, 16h+16) to both operands,
+// so one ds_read_b128 serves four MFMA steps (the order of the k-summation is
+// free).  Accumulator element v of lane l is row 8*(v/4) + 4*(l/32) + v%4,
+// column l%32 of its 32x32 block.
+__device__ __forceinline__ void gemm_tile(const float *__restrict__ Q, int64_t nq, int64_t q0,
+                                          const float *__restrict__ C, int64_t K, int64_t c0, int D,
+                                          float *As, float *Bs, floatx16 (&acc)[2][2])
 {
-    __shared__ __attribute__((aligned(16))) float As[GT * GLD];
-    __shared__ __attribute__((aligned(16))) float Bs[GT * GLD];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int64_t tile = blockIdx.x;
-    const int64_t q0 = (tile % tiles_q) * GT, c0 = (tile / tiles_q) * GT;
     const int wq = (wave >> 1) * 64, wc = (wave & 1) * 64;
     const int l32 = lane & 31, h = lane >> 5;
-
-    floatx16 acc[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -90,8 +82,25 @@ __global__ __launch_bounds__(256) void coarse_gemm_kernel(
         }
         __syncthreads();
     }
+}
 
-    // accumulator element v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32
+// Dt[q][j] = max(0, qn[q] + cn[j] - 2 <Q[q], C[j]>).  Tiles are numbered
+// centroid-tile-major so that the query tiles (small, L2 resident) are swept
+// against one centroid tile after the other.
+__global__ __launch_bounds__(256) void coarse_gemm_kernel(
+    const float *__restrict__ Q, const float *__restrict__ qn, int64_t nq,
+    const float *__restrict__ C, const float *__restrict__ cn, int64_t K, int D,
+    float *__restrict__ Dt, int tiles_q)
+{
+    __shared__ __attribute__((aligned(16))) float As[GT * GLD];
+    __shared__ __attribute__((aligned(16))) float Bs[GT * GLD];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t tile = blockIdx.x;
+    const int64_t q0 = (tile % tiles_q) * GT, c0 = (tile / tiles_q) * GT;
+    const int wq = (wave >> 1) * 64, wc = (wave & 1) * 64;
+    const int l32 = lane & 31, h = lane >> 5;
+    floatx16 acc[2][2];
+    gemm_tile(Q, nq, q0, C, K, c0, D, As, Bs, acc);
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         int64_t col = c0 + wc + j * 32 + l32;
@@ -108,6 +117,65 @@ __global__ __launch_bounds__(256) void coarse_gemm_kernel(
                 }
             }
     }
+}
+
+// Nearest centroid only (P = 1): the same tile product, reduced on the fly to
+// the per-row minimum of (distance, centroid id), merged across centroid tiles
+// with a 64-bit atomic minimum; no distance tile is written.  best[] must be
+// pre-filled with all ones.
+__global__ __launch_bounds__(256) void coarse_argmin_kernel(
+    const float *__restrict__ Q, const float *__restrict__ qn, int64_t nq,
+    const float *__restrict__ C, const float *__restrict__ cn, int64_t K, int D,
+    unsigned long long *__restrict__ best, int tiles_q)
+{
+    __shared__ __attribute__((aligned(16))) float As[GT * GLD];
+    __shared__ __attribute__((aligned(16))) float Bs[GT * GLD];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t tile = blockIdx.x;
+    const int64_t q0 = (tile % tiles_q) * GT, c0 = (tile / tiles_q) * GT;
+    const int wq = (wave >> 1) * 64, wc = (wave & 1) * 64;
+    const int l32 = lane & 31, h = lane >> 5;
+    floatx16 acc[2][2];
+    gemm_tile(Q, nq, q0, C, K, c0, D, As, Bs, acc);
+    float cnj[2];
+    int64_t col[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        col[j] = c0 + wc + j * 32 + l32;
+        cnj[j] = col[j] < K ? cn[col[j]] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            int64_t row = q0 + wq + i * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+            float qr = row < nq ? qn[row] : 0.f;
+            unsigned long long key = ~0ull;
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                if (col[j] < K) {
+                    float d = fmaxf(fmaf(-2.f, acc[i][j][v], qr + cnj[j]), 0.f);
+                    unsigned long long kj = ((unsigned long long)float_key(d) << 32) | (uint32_t)col[j];
+                    key = kj < key ? kj : key;
+                }
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1) {   // stays inside the 32-lane half that shares the row
+                unsigned long long t = __shfl_xor(key, o, WAVE);
+                key = t < key ? t : key;
+            }
+            if (l32 == 0 && row < nq) atomicMin(&best[row], key);
+        }
+}
+
+__global__ __launch_bounds__(256) void argmin_unpack_kernel(const unsigned long long *__restrict__ best,
+                                                            int64_t n, int32_t *__restrict__ out_id,
+                                                            float *__restrict__ out_d)
+{
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    unsigned long long k = best[i];
+    out_id[i] = (int32_t)(uint32_t)k;
+    if (out_d) out_d[i] = key_float((uint32_t)(k >> 32));
 }
 
 // The P closest centroids of each query row of Dt by (distance, id), written

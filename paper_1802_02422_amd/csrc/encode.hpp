@@ -12,7 +12,8 @@ __global__ __launch_bounds__(64) void encode_kernel(
     const float *__restrict__ C, const int32_t *__restrict__ nbr, const float *__restrict__ alpha,
     const float *__restrict__ cs_dist2, const float *__restrict__ codebook,
     const float *__restrict__ const_table, int32_t *__restrict__ out_sub,
-    uint8_t *__restrict__ out_codes, uint8_t *__restrict__ out_byte, float *__restrict__ out_t)
+    uint8_t *__restrict__ out_codes, uint8_t *__restrict__ out_byte, float *__restrict__ out_t,
+    float *__restrict__ out_res)
 {
     extern __shared__ float sm[];
     float *xs = sm, *cs = sm + D, *es = sm + 2 * D, *mus = sm + 3 * D;
@@ -59,8 +60,10 @@ __global__ __launch_bounds__(64) void encode_kernel(
         float mu = fmaf(a, s[t] - cs[t], cs[t]);
         mus[t] = mu;
         es[t] = xs[t] - mu;
+        if (out_res) out_res[i * D + t] = xs[t] - mu;
     }
     wave_sync();
+    if (!codebook) return;   // trained up to alpha only: region / subregion / displacement
 
     // PQ: nearest of the 256 codewords per block of D/M dims, lowest index on ties
     const int ds = D / M;

@@ -8,6 +8,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <vector>
 
 #include <hip/hip_runtime.h>
 #include <rocprim/device/device_scan.hpp>
@@ -86,10 +87,9 @@ int check_trained(const ivf_index_desc *d)
     if (d->L < 1 || d->K < 1) return fail(IVF_EINVAL, "K=%lld and L=%d must be positive", (long long)d->K, d->L);
     if ((int64_t)d->L >= d->K && d->K > 1) return fail(IVF_EINVAL, "L=%d needs at least L+1 centroids", d->L);
     if (d->K * (int64_t)d->L >= (1ll << 31)) return fail(IVF_EINVAL, "K*L must be below 2^31");
-    if (!d->centroids || !d->nbr || !d->alpha || !d->cs_dist2 || !d->pq_codebook)
-        return fail(IVF_EINVAL, "a trained array (centroids, nbr, alpha, cs_dist2, pq_codebook) is NULL");
-    if (!aligned16(d->centroids) || !aligned16(d->pq_codebook))
-        return fail(IVF_EINVAL, "centroids and pq_codebook must be 16-byte aligned");
+    if (!d->centroids || !d->nbr || !d->alpha || !d->cs_dist2)
+        return fail(IVF_EINVAL, "a trained array (centroids, nbr, alpha, cs_dist2) is NULL");
+    if (!aligned16(d->centroids)) return fail(IVF_EINVAL, "centroids must be 16-byte aligned");
     return IVF_OK;
 }
 
@@ -129,6 +129,10 @@ struct ivf_index {
     uint8_t *blocks = nullptr;
     int64_t scratch_limit = 8ll << 30;
     Buf dt, qn, probe_id, probe_d, scores, desc, lut, partial;
+    // optional per-stage timing with HIP events on the caller's stream
+    bool profile = false;
+    std::vector<hipEvent_t> ev[IVF_N_STAGES + 1];   // ev[s][i], ev[s+1][i] bracket stage s of pass i
+    int64_t launches = 0;
 };
 
 extern "C" const char *ivf_last_error(void) { return g_err.c_str(); }
@@ -230,8 +234,8 @@ extern "C" int ivf_load_index(const ivf_index_desc *d, void *hip_stream, ivf_ind
     int rc = check_trained(d);
     if (rc) return rc;
     if (!out) return fail(IVF_EINVAL, "out is NULL");
-    if (!d->const_table || !d->sub_offsets || !d->codes || !d->const_byte || !d->ids)
-        return fail(IVF_EINVAL, "an encoded array (const_table, sub_offsets, codes, const_byte, ids) is NULL");
+    if (!d->pq_codebook || !d->const_table || !d->sub_offsets || !d->codes || !d->const_byte || !d->ids)
+        return fail(IVF_EINVAL, "pq_codebook or an encoded array (const_table, sub_offsets, codes, const_byte, ids) is NULL");
     if (d->N < 0 || d->N >= (1ll << 32)) return fail(IVF_EINVAL, "N=%lld out of range", (long long)d->N);
     if (!aligned16(d->codes)) return fail(IVF_EINVAL, "codes must be 16-byte aligned");
     ivf_index *ix = new (std::nothrow) ivf_index;
@@ -314,15 +318,27 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
         float *lut = static_cast<float *>(ix->lut.p);
         uint64_t *partial = static_cast<uint64_t *>(ix->partial.p);
 
+        auto mark = [&](int stage) -> int {
+            if (!ix->profile) return IVF_OK;
+            hipEvent_t e;
+            HIPCHK(hipEventCreate(&e));
+            HIPCHK(hipEventRecord(e, st));
+            ix->ev[stage].push_back(e);
+            return IVF_OK;
+        };
+        if ((rc = mark(0))) return rc;
         row_norm_kernel<<<dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st>>>(Q, n, D, qn);
         LAUNCHCHK("row_norm_kernel");
         if ((rc = launch_coarse(Q, qn, n, ix->centroids, ix->cnorm, K, D, Dt, st))) return rc;
+        if ((rc = mark(1))) return rc;
         if ((rc = launch_probe_select(Dt, n, K, P, pid, pd, st))) return rc;
+        if ((rc = mark(2))) return rc;
 
         const int64_t total = n * PL;
         score_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
             Dt, K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, scores, total);
         LAUNCHCHK("score_kernel");
+        if ((rc = mark(3))) return rc;
 
         int64_t *ks = kept_sub_out ? kept_sub_out + q0 * S : nullptr;
         int64_t *ns = n_scanned_out ? n_scanned_out + q0 : nullptr;
@@ -333,9 +349,11 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
             prune_kernel<256><<<dim3((unsigned)n), dim3(256), 0, st>>>(
                 scores, (int)PL, S, pid, P, L, ix->sub_offsets, ix->blk_off, desc, ks, ns);
         LAUNCHCHK("prune_kernel");
+        if ((rc = mark(4))) return rc;
 
         lut_kernel<<<dim3((unsigned)n), dim3(256), (size_t)D * sizeof(float), st>>>(Q, D, M, ix->codebook, lut);
         LAUNCHCHK("lut_kernel");
+        if ((rc = mark(5))) return rc;
 
         if (M == 16)
             scan_kernel<16><<<dim3((unsigned)(n * nsplit)), dim3(SCAN_BLOCK), scan_lds, st>>>(
@@ -344,11 +362,43 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
             scan_kernel<8><<<dim3((unsigned)(n * nsplit)), dim3(SCAN_BLOCK), scan_lds, st>>>(
                 ix->blocks, ix->ids, ix->const_table, desc, S, lut, k, nsplit, partial);
         LAUNCHCHK("scan_kernel");
+        if ((rc = mark(6))) return rc;
 
         merge_kernel<256><<<dim3((unsigned)n), dim3(256), merge_lds, st>>>(
             partial, merge_n, merge_pow2, k, out_ids + q0 * k, out_dists + q0 * k);
         LAUNCHCHK("merge_kernel");
+        if ((rc = mark(7))) return rc;
+        if (ix->profile) ix->launches++;
     }
+    return IVF_OK;
+}
+
+extern "C" int ivf_profile_enable(ivf_index *ix, int on)
+{
+    if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    ix->profile = on != 0;
+    return IVF_OK;
+}
+
+extern "C" int ivf_profile_read(ivf_index *ix, double *stage_ms, int64_t *launches)
+{
+    if (!ix || !stage_ms || !launches) return fail(IVF_EINVAL, "NULL argument");
+    HIPCHK(hipDeviceSynchronize());
+    for (int s = 0; s < IVF_N_STAGES; ++s) {
+        double tot = 0.0;
+        for (size_t i = 0; i < ix->ev[s].size() && i < ix->ev[s + 1].size(); ++i) {
+            float ms = 0.f;
+            HIPCHK(hipEventElapsedTime(&ms, ix->ev[s][i], ix->ev[s + 1][i]));
+            tot += ms;
+        }
+        stage_ms[s] = tot;
+    }
+    *launches = ix->launches;
+    for (int s = 0; s <= IVF_N_STAGES; ++s) {
+        for (hipEvent_t e : ix->ev[s]) (void)hipEventDestroy(e);
+        ix->ev[s].clear();
+    }
+    ix->launches = 0;
     return IVF_OK;
 }
 
@@ -377,10 +427,32 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
     int rc = IVF_OK;
     auto body = [&]() -> int {
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&cn), (size_t)K * sizeof(float)));
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), (size_t)tile * sizeof(float)));
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&Dt), (size_t)tile * K * sizeof(float)));
         row_norm_kernel<<<dim3((unsigned)((K + 3) / 4)), dim3(256), 0, st>>>(centroids, K, D, cn);
         LAUNCHCHK("row_norm_kernel");
+        if (P == 1) {   // fused per-row minimum, no distance tile
+            const int64_t chunk = 1 << 20;
+            unsigned long long *best = nullptr;
+            HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), (size_t)(nq < chunk ? nq : chunk) * sizeof(float)));
+            HIPCHK(hipMalloc(reinterpret_cast<void **>(&Dt), (size_t)(nq < chunk ? nq : chunk) * sizeof(unsigned long long)));
+            best = reinterpret_cast<unsigned long long *>(Dt);
+            for (int64_t q0 = 0; q0 < nq; q0 += chunk) {
+                const int64_t n = (nq - q0 < chunk) ? nq - q0 : chunk;
+                HIPCHK(hipMemsetAsync(best, 0xFF, (size_t)n * sizeof(unsigned long long), st));
+                row_norm_kernel<<<dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st>>>(x + q0 * D, n, D, xn);
+                LAUNCHCHK("row_norm_kernel");
+                int tiles_q = (int)((n + GT - 1) / GT);
+                int64_t grid = tiles_q * ((K + GT - 1) / GT);
+                if (grid >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
+                coarse_argmin_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(x + q0 * D, xn, n, centroids, cn, K, D, best, tiles_q);
+                LAUNCHCHK("coarse_argmin_kernel");
+                argmin_unpack_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(best, n, out_id + q0, out_d + q0);
+                LAUNCHCHK("argmin_unpack_kernel");
+            }
+            HIPCHK(hipStreamSynchronize(st));
+            return IVF_OK;
+        }
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), (size_t)tile * sizeof(float)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&Dt), (size_t)tile * K * sizeof(float)));
         for (int64_t q0 = 0; q0 < nq; q0 += tile) {
             const int64_t n = (nq - q0 < tile) ? nq - q0 : tile;
             row_norm_kernel<<<dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st>>>(x + q0 * D, n, D, xn);
@@ -404,12 +476,15 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
 
 extern "C" int ivf_encode(const ivf_index_desc *t, const float *x, int64_t n, const int32_t *region_in,
                           int32_t *out_region, int32_t *out_sub, uint8_t *out_codes,
-                          uint8_t *out_const_byte, float *out_const_t, void *hip_stream)
+                          uint8_t *out_const_byte, float *out_const_t, float *out_residual,
+                          void *hip_stream)
 {
     int rc = check_trained(t);
     if (rc) return rc;
-    if (!x || !out_region || !out_sub || !out_codes) return fail(IVF_EINVAL, "NULL argument");
-    if (t->const_table && !out_const_byte) return fail(IVF_EINVAL, "out_const_byte is NULL");
+    if (!x || !out_region || !out_sub) return fail(IVF_EINVAL, "NULL argument");
+    if (t->pq_codebook && !out_codes) return fail(IVF_EINVAL, "out_codes is NULL");
+    if (t->pq_codebook && !aligned16(t->pq_codebook)) return fail(IVF_EINVAL, "pq_codebook must be 16-byte aligned");
+    if (t->pq_codebook && t->const_table && !out_const_byte) return fail(IVF_EINVAL, "out_const_byte is NULL");
     if (!aligned16(x)) return fail(IVF_EINVAL, "x must be 16-byte aligned");
     if (n < 0 || n >= (1ll << 31)) return fail(IVF_EINVAL, "n out of range");
     if (n == 0) return IVF_OK;
@@ -428,7 +503,7 @@ extern "C" int ivf_encode(const ivf_index_desc *t, const float *x, int64_t n, co
     }
     encode_kernel<<<dim3((unsigned)n), dim3(64), (size_t)4 * t->D * sizeof(float), st>>>(
         x, n, t->D, t->M, t->L, out_region, t->centroids, t->nbr, t->alpha, t->cs_dist2, t->pq_codebook,
-        t->const_table, out_sub, out_codes, out_const_byte, out_const_t);
+        t->const_table, out_sub, out_codes, out_const_byte, out_const_t, out_residual);
     LAUNCHCHK("encode_kernel");
     HIPCHK(hipStreamSynchronize(st));
     return IVF_OK;

@@ -26,7 +26,8 @@ U = 2.0 ** -24
 def to_device(ix, with_codes=True):
     dev = torch.device("cuda:0")
     t = lambda a, dt=None: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-    d = ivf.IndexDesc(t(ix.centroids), t(ix.nbr), t(ix.alpha), t(ix.cs_dist2), t(ix.pq_codebook), t(ix.const_table))
+    d = ivf.IndexDesc(t(ix.centroids), t(ix.nbr), t(ix.alpha), t(ix.cs_dist2), t(ix.pq_codebook),
+                      const_table=t(ix.const_table))
     if with_codes:
         d.sub_offsets = t(ix.sub_offsets.view(np.int32))
         d.codes = t(ix.codes)
