@@ -275,8 +275,8 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
     // queries per pass: bounded by the distance tile
     int64_t tile = ix->scratch_limit / (K * (int64_t)sizeof(float));
     if (tile < 1) tile = 1;
-    if (tile > nq) tile = nq;
-    if (tile >= GT) tile -= tile % GT;
+    if (tile >= nq) tile = nq;
+    else if (tile >= GT) tile -= tile % GT;
 
     // workgroups per query in the scan: fill the chip when the batch is small
     int nsplit = (int)((2048 + tile - 1) / tile);
@@ -421,8 +421,8 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     int64_t tile = (4ll << 30) / (K * (int64_t)sizeof(float));
     if (tile < 1) tile = 1;
-    if (tile > nq) tile = nq;
-    if (tile >= GT) tile -= tile % GT;
+    if (tile >= nq) tile = nq;
+    else if (tile >= GT) tile -= tile % GT;
     float *cn = nullptr, *xn = nullptr, *Dt = nullptr;
     int rc = IVF_OK;
     auto body = [&]() -> int {
