@@ -84,13 +84,16 @@ __device__ __forceinline__ void gemm_tile(const float *__restrict__ Q, int64_t n
     }
 }
 
-// Dt[q][j] = max(0, qn[q] + cn[j] - 2 <Q[q], C[j]>).  Tiles are numbered
-// centroid-tile-major so that the query tiles (small, L2 resident) are swept
-// against one centroid tile after the other.
+constexpr int BMW = 64;   // centroids per block minimum
+
+// Dt[q][j] = max(0, qn[q] + cn[j] - 2 <Q[q], C[j]>), and bm[q][b] = the minimum
+// of Dt[q][64b .. 64b+63] (each wavefront's 64-column quadrant gives one block
+// minimum per row).  Tiles are numbered centroid-tile-major so that the query
+// tiles (small, L2 resident) are swept against one centroid tile after the other.
 __global__ __launch_bounds__(256) void coarse_gemm_kernel(
     const float *__restrict__ Q, const float *__restrict__ qn, int64_t nq,
     const float *__restrict__ C, const float *__restrict__ cn, int64_t K, int D,
-    float *__restrict__ Dt, int tiles_q)
+    float *__restrict__ Dt, float *__restrict__ bm, int nb, int tiles_q)
 {
     __shared__ __attribute__((aligned(16))) float As[GT * GLD];
     __shared__ __attribute__((aligned(16))) float Bs[GT * GLD];
@@ -101,22 +104,32 @@ __global__ __launch_bounds__(256) void coarse_gemm_kernel(
     const int l32 = lane & 31, h = lane >> 5;
     floatx16 acc[2][2];
     gemm_tile(Q, nq, q0, C, K, c0, D, As, Bs, acc);
+    float cnj[2];
+    int64_t col[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        int64_t col = c0 + wc + j * 32 + l32;
-        if (col >= K) continue;
-        float cnj = cn[col];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int64_t row = q0 + wq + i * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-                if (row < nq) {
-                    float d = fmaf(-2.f, acc[i][j][v], qn[row] + cnj);
-                    Dt[row * K + col] = fmaxf(d, 0.f);
-                }
-            }
+        col[j] = c0 + wc + j * 32 + l32;
+        cnj[j] = col[j] < K ? cn[col[j]] : 0.f;
     }
+    const int64_t blk = (c0 + wc) / BMW;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            int64_t row = q0 + wq + i * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+            float qr = row < nq ? qn[row] : 0.f;
+            float m = INFINITY;
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                if (col[j] < K) {
+                    float d = fmaxf(fmaf(-2.f, acc[i][j][v], qr + cnj[j]), 0.f);
+                    if (row < nq) Dt[row * K + col[j]] = d;
+                    m = fminf(m, d);
+                }
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1) m = fminf(m, __shfl_xor(m, o, WAVE));
+            if (l32 == 0 && row < nq && blk < nb) bm[row * nb + blk] = m;
+        }
 }
 
 // Nearest centroid only (P = 1): the same tile product, reduced on the fly to
@@ -179,21 +192,48 @@ __global__ __launch_bounds__(256) void argmin_unpack_kernel(const unsigned long 
 }
 
 // The P closest centroids of each query row of Dt by (distance, id), written
-// in ascending centroid id.  One workgroup per query.
+// in ascending centroid id.  One workgroup per query, in three steps:
+//   1. t = the min(P, nb)-th smallest block minimum.  The P smallest block
+//      minima are P distinct distances <= t, so every one of the P closest
+//      centroids has distance <= t and lies in a block whose minimum is <= t.
+//   2. list, in ascending order, every block with minimum < t (fewer than P)
+//      and the first P blocks with minimum == t (a later such block is
+//      preceded by at least P distances equal to t, so it cannot contribute).
+//   3. exact radix select of the P smallest (distance, id) among the
+//      elements of the listed blocks (at most 2P*64), read from Dt.
+// blist is dynamic LDS of 2*P ints.
 template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void probe_select_kernel(const float *__restrict__ Dt, int64_t K,
-                                                             int P, int32_t *__restrict__ probe_id,
+__global__ __launch_bounds__(BLOCK) void probe_select_kernel(const float *__restrict__ Dt,
+                                                             const float *__restrict__ bm, int64_t K,
+                                                             int nb, int P,
+                                                             int32_t *__restrict__ probe_id,
                                                              float *__restrict__ probe_d)
 {
     __shared__ SelectShared sh;
+    __shared__ uint32_t nflag_s;
+    extern __shared__ int blist[];
     const int64_t q = blockIdx.x;
     const float *row = Dt + q * K;
-    auto key = [row](int64_t i) { return float_key(row[i]); };
+    const float *bmr = bm + q * nb;
+    auto keyb = [bmr](int64_t b) { return float_key(bmr[b]); };
+    const uint32_t nselb = P < nb ? (uint32_t)P : (uint32_t)nb;
+    uint32_t t, needb;
+    block_radix_select<BLOCK>(keyb, nb, nselb, sh, t, needb);
+    uint32_t nflag = block_emit_selected<BLOCK>(keyb, nb, 0xFFFFFFFFu, t, (uint32_t)P, sh,
+                                                [&](uint32_t pos, int64_t b, uint32_t) { blist[pos] = (int)b; });
+    if (threadIdx.x == 0) nflag_s = nflag;
+    __syncthreads();
+    nflag = nflag_s;
+    auto keyv = [row, K](int64_t v, const int *bl) {
+        int64_t c = (int64_t)bl[v >> 6] * BMW + (v & 63);
+        return c < K ? float_key(row[c]) : 0xFFFFFFFFu;
+    };
+    auto key = [&](int64_t v) { return keyv(v, blist); };
     uint32_t pivot, need;
-    block_radix_select<BLOCK>(key, K, (uint32_t)P, sh, pivot, need);
-    block_emit_selected<BLOCK>(key, K, (uint32_t)P, pivot, need, sh,
-                               [&](uint32_t pos, int64_t i, uint32_t k) {
-                                   probe_id[q * P + pos] = (int32_t)i;
+    block_radix_select<BLOCK>(key, (int64_t)nflag * BMW, (uint32_t)P, sh, pivot, need);
+    block_emit_selected<BLOCK>(key, (int64_t)nflag * BMW, (uint32_t)P, pivot, need, sh,
+                               [&](uint32_t pos, int64_t v, uint32_t k) {
+                                   probe_id[q * P + pos] = blist[v >> 6] * BMW + (int)(v & 63);
                                    probe_d[q * P + pos] = key_float(k);
                                });
 }

@@ -95,24 +95,27 @@ int check_trained(const ivf_index_desc *d)
 
 // ------------------------------------------------------------ stage 1 driver
 int launch_coarse(const float *x, const float *xn, int64_t nq, const float *C, const float *cn,
-                  int64_t K, int D, float *Dt, hipStream_t st)
+                  int64_t K, int D, float *Dt, float *bm, hipStream_t st)
 {
+    const int nb = (int)((K + BMW - 1) / BMW);
     int tiles_q = (int)((nq + GT - 1) / GT);
     int64_t tiles_c = (K + GT - 1) / GT;
     int64_t grid = tiles_q * tiles_c;
     if (grid >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
-    coarse_gemm_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(x, xn, nq, C, cn, K, D, Dt, tiles_q);
+    coarse_gemm_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(x, xn, nq, C, cn, K, D, Dt, bm, nb, tiles_q);
     LAUNCHCHK("coarse_gemm_kernel");
     return IVF_OK;
 }
 
-int launch_probe_select(const float *Dt, int64_t nq, int64_t K, int P, int32_t *pid, float *pd,
-                        hipStream_t st)
+int launch_probe_select(const float *Dt, const float *bm, int64_t nq, int64_t K, int P, int32_t *pid,
+                        float *pd, hipStream_t st)
 {
-    if (K >= 16384)
-        probe_select_kernel<1024><<<dim3((unsigned)nq), dim3(1024), 0, st>>>(Dt, K, P, pid, pd);
+    const int nb = (int)((K + BMW - 1) / BMW);
+    const size_t lds = (size_t)2 * P * sizeof(int);
+    if (P >= 1024)
+        probe_select_kernel<1024><<<dim3((unsigned)nq), dim3(1024), lds, st>>>(Dt, bm, K, nb, P, pid, pd);
     else
-        probe_select_kernel<256><<<dim3((unsigned)nq), dim3(256), 0, st>>>(Dt, K, P, pid, pd);
+        probe_select_kernel<256><<<dim3((unsigned)nq), dim3(256), lds, st>>>(Dt, bm, K, nb, P, pid, pd);
     LAUNCHCHK("probe_select_kernel");
     return IVF_OK;
 }
@@ -128,7 +131,7 @@ struct ivf_index {
     uint32_t *sub_offsets = nullptr, *blk_off = nullptr;
     uint8_t *blocks = nullptr;
     int64_t scratch_limit = 8ll << 30;
-    Buf dt, qn, probe_id, probe_d, scores, desc, lut, partial;
+    Buf dt, bm, qn, probe_id, probe_d, scores, desc, lut, partial;
     // optional per-stage timing with HIP events on the caller's stream
     bool profile = false;
     std::vector<hipEvent_t> ev[IVF_N_STAGES + 1];   // ev[s][i], ev[s+1][i] bracket stage s of pass i
@@ -151,7 +154,7 @@ extern "C" void ivf_free_index(ivf_index *ix)
     if (!ix) return;
     (void)hipDeviceSynchronize();
     void *owned[] = {ix->centroids, ix->cnorm, ix->alpha, ix->cst, ix->codebook, ix->const_table,
-                     ix->nbr, ix->ids, ix->sub_offsets, ix->blk_off, ix->blocks, ix->dt.p, ix->qn.p,
+                     ix->nbr, ix->ids, ix->sub_offsets, ix->blk_off, ix->blocks, ix->dt.p, ix->bm.p, ix->qn.p,
                      ix->probe_id.p, ix->probe_d.p, ix->scores.p, ix->desc.p, ix->lut.p, ix->partial.p};
     for (void *p : owned)
         if (p) (void)hipFree(p);
@@ -289,6 +292,8 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
 
     int rc;
     if ((rc = ensure(ix->dt, (size_t)tile * K * sizeof(float)))) return rc;
+    const int64_t nb = (K + BMW - 1) / BMW;
+    if ((rc = ensure(ix->bm, (size_t)tile * nb * sizeof(float)))) return rc;
     if ((rc = ensure(ix->qn, (size_t)tile * sizeof(float)))) return rc;
     if ((rc = ensure(ix->probe_id, (size_t)tile * P * sizeof(int32_t)))) return rc;
     if ((rc = ensure(ix->probe_d, (size_t)tile * P * sizeof(float)))) return rc;
@@ -311,6 +316,7 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
         const float *Q = queries + q0 * D;
         float *Dt = static_cast<float *>(ix->dt.p);
         float *qn = static_cast<float *>(ix->qn.p);
+        float *bm = static_cast<float *>(ix->bm.p);
         int32_t *pid = probe_id_out ? probe_id_out + q0 * P : static_cast<int32_t *>(ix->probe_id.p);
         float *pd = probe_d_out ? probe_d_out + q0 * P : static_cast<float *>(ix->probe_d.p);
         float *scores = static_cast<float *>(ix->scores.p);
@@ -329,9 +335,9 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
         if ((rc = mark(0))) return rc;
         row_norm_kernel<<<dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st>>>(Q, n, D, qn);
         LAUNCHCHK("row_norm_kernel");
-        if ((rc = launch_coarse(Q, qn, n, ix->centroids, ix->cnorm, K, D, Dt, st))) return rc;
+        if ((rc = launch_coarse(Q, qn, n, ix->centroids, ix->cnorm, K, D, Dt, bm, st))) return rc;
         if ((rc = mark(1))) return rc;
-        if ((rc = launch_probe_select(Dt, n, K, P, pid, pd, st))) return rc;
+        if ((rc = launch_probe_select(Dt, bm, n, K, P, pid, pd, st))) return rc;
         if ((rc = mark(2))) return rc;
 
         const int64_t total = n * PL;
@@ -414,7 +420,7 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
 {
     if (!centroids || !x || !out_id || !out_d) return fail(IVF_EINVAL, "NULL argument");
     if (D < 4 || D % 4 || D > IVF_MAX_D) return fail(IVF_EINVAL, "D=%d must be a multiple of 4", D);
-    if (K < 1 || P < 1 || P > K) return fail(IVF_EINVAL, "need 1 <= P <= K");
+    if (K < 1 || P < 1 || P > K || P > 4096) return fail(IVF_EINVAL, "need 1 <= P <= min(K, 4096)");
     if (nq < 0 || nq >= (1ll << 31)) return fail(IVF_EINVAL, "nq out of range");
     if (!aligned16(centroids) || !aligned16(x)) return fail(IVF_EINVAL, "centroids and x must be 16-byte aligned");
     if (nq == 0) return IVF_OK;
@@ -423,7 +429,8 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
     if (tile < 1) tile = 1;
     if (tile >= nq) tile = nq;
     else if (tile >= GT) tile -= tile % GT;
-    float *cn = nullptr, *xn = nullptr, *Dt = nullptr;
+    float *cn = nullptr, *xn = nullptr, *Dt = nullptr, *bm = nullptr;
+    const int64_t nb = (K + BMW - 1) / BMW;
     int rc = IVF_OK;
     auto body = [&]() -> int {
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&cn), (size_t)K * sizeof(float)));
@@ -453,13 +460,14 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
         }
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), (size_t)tile * sizeof(float)));
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&Dt), (size_t)tile * K * sizeof(float)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&bm), (size_t)tile * nb * sizeof(float)));
         for (int64_t q0 = 0; q0 < nq; q0 += tile) {
             const int64_t n = (nq - q0 < tile) ? nq - q0 : tile;
             row_norm_kernel<<<dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st>>>(x + q0 * D, n, D, xn);
             LAUNCHCHK("row_norm_kernel");
             int r2;
-            if ((r2 = launch_coarse(x + q0 * D, xn, n, centroids, cn, K, D, Dt, st))) return r2;
-            if ((r2 = launch_probe_select(Dt, n, K, P, out_id + q0 * P, out_d + q0 * P, st))) return r2;
+            if ((r2 = launch_coarse(x + q0 * D, xn, n, centroids, cn, K, D, Dt, bm, st))) return r2;
+            if ((r2 = launch_probe_select(Dt, bm, n, K, P, out_id + q0 * P, out_d + q0 * P, st))) return r2;
         }
         HIPCHK(hipStreamSynchronize(st));
         return IVF_OK;
@@ -470,6 +478,7 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
     if (cn) (void)hipFree(cn);
     if (xn) (void)hipFree(xn);
     if (Dt) (void)hipFree(Dt);
+    if (bm) (void)hipFree(bm);
     g_err = keep;
     return rc;
 }

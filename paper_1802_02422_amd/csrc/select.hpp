@@ -58,11 +58,13 @@ __device__ void block_radix_select(KeyFn key, int64_t n, uint32_t nsel, SelectSh
     need = remaining;
 }
 
-// Calls emit(out_pos, i, key) for every selected item i, where out_pos is the
-// item's rank among the selected ones in ascending i.
+// Calls emit(out_pos, i, key) for every item with key < pivot and for the
+// `need` lowest-positioned items with key == pivot, where out_pos is the item's
+// rank among the emitted ones in ascending i.  Stops early once nsel items
+// have been emitted.  Returns the number emitted.
 template <int BLOCK, class KeyFn, class EmitFn>
-__device__ void block_emit_selected(KeyFn key, int64_t n, uint32_t nsel, uint32_t pivot,
-                                    uint32_t need, SelectShared &sh, EmitFn emit)
+__device__ uint32_t block_emit_selected(KeyFn key, int64_t n, uint32_t nsel, uint32_t pivot,
+                                        uint32_t need, SelectShared &sh, EmitFn emit)
 {
     const int tid = threadIdx.x;
     uint32_t run_lt = 0, run_eq = 0;
@@ -83,6 +85,7 @@ __device__ void block_emit_selected(KeyFn key, int64_t n, uint32_t nsel, uint32_
         run_eq += total >> 16;
         if (run_lt + (run_eq < need ? run_eq : need) >= nsel) break;   // uniform
     }
+    return run_lt + (run_eq < need ? run_eq : need);
 }
 
 // In-place ascending bitonic sort of n (a power of two) uint64 keys in LDS by
