@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--workload", default=os.environ.get("IVF_BENCH_WORKLOAD", "deep1b"))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scratch-gib", type=float, default=48.0)
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run the plain 1 GiB copy kernel (reference for rocprofv3 HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1",
@@ -128,6 +130,22 @@ def main():
     achieved = algo_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
     coarse_tflops = 2.0 * spec.nq * spec.K * spec.D * args.steps / (stage_ms["coarse_gemm"] * 1e-3) / 1e12
 
+    copy_gbs = None
+    if args.calibrate:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        b = torch.empty_like(a)
+        ivf.ivf_copy_bytes(b, a)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            ivf.ivf_copy_bytes(b, a)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 3 * 2 * a.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9     # read + write
+        log(f"copy kernel: {copy_gbs:.0f} GB/s (read+write) on 1 GiB")
+        del a, b
+
     result = {
         "metric": "queries/s at fixed nprobe/prune budget; ADC codes scanned/s (HBM GB/s)",
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -144,6 +162,8 @@ def main():
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "launches": scan_launches, "avg_launch_ms": scan_ms, "algorithmic_bytes_per_launch": algo_bytes},
     }
+    if copy_gbs is not None:
+        result["copy_kernel_gbs_read_plus_write"] = copy_gbs
     if host_ix is not None:
         result["cpu_baseline"] = cpu_baseline(host_ix, Q.cpu().numpy(), spec)
     print(json.dumps(result), flush=True)

@@ -186,6 +186,14 @@ int ivf_alpha_stats(const float *centroids, int64_t K, int D, const int32_t *nbr
 int ivf_profile_enable(ivf_index *index, int on);
 int ivf_profile_read(ivf_index *index, double *stage_ms, int64_t *launches);
 
+/*
+ * Plain device-to-device streaming copy by a grid-stride kernel of 128-bit
+ * loads and stores (nbytes a multiple of 16, both pointers 16-byte aligned).
+ * It reads and writes exactly nbytes: the reference against which hardware
+ * HBM counters and the scan's bandwidth are calibrated.  Asynchronous.
+ */
+int ivf_copy_bytes(void *dst, const void *src, int64_t nbytes, void *hip_stream);
+
 /* Message of the last error on this host thread ("" if none). */
 const char *ivf_last_error(void);
 

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     ivf_alpha_stats,
     ivf_last_error,
     ivf_profile_enable,
+    ivf_copy_bytes,
     ivf_profile_read,
     STAGE_NAMES,
 )

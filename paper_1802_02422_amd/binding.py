@@ -58,6 +58,7 @@ def load_library():
     lib.ivf_alpha_stats.argtypes = [vp, i64, i32, vp, i32, vp, i64, vp, vp, vp, vp]
     lib.ivf_profile_enable.argtypes = [vp, i32]
     lib.ivf_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
+    lib.ivf_copy_bytes.argtypes = [vp, vp, i64, vp]
     lib.ivf_last_error.restype = C.c_char_p
     _lib = lib
     return lib
@@ -267,3 +268,11 @@ def ivf_profile_read(index: IndexHandle):
     n = C.c_int64()
     _check(load_library().ivf_profile_read(index.ptr, ms, C.byref(n)))
     return dict(zip(STAGE_NAMES, list(ms))), n.value
+
+
+def ivf_copy_bytes(dst: torch.Tensor, src: torch.Tensor) -> None:
+    """Streaming copy of src's bytes into dst (same byte size, multiple of 16)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (src.is_cuda and dst.is_cuda):
+        raise IvfError("ivf_copy_bytes: device tensors of equal byte size expected")
+    _check(load_library().ivf_copy_bytes(_ptr(dst), _ptr(src), nbytes, _stream()))

@@ -302,8 +302,8 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
     if ((rc = ensure(ix->lut, (size_t)tile * M * 256 * sizeof(float)))) return rc;
     if ((rc = ensure(ix->partial, (size_t)tile * merge_n * sizeof(uint64_t)))) return rc;
 
-    const size_t scan_lds = (size_t)(M * 256 + 256) * sizeof(float) +
-                            (size_t)SCAN_WAVES * pool_capacity(k) * sizeof(uint64_t);
+    const size_t scan_lds = (size_t)(M * 256 + 256) * sizeof(float) + SCAN_WAVES * sizeof(WaveStage) +
+                            (size_t)SCAN_WAVES * pool_capacity(k) * sizeof(uint64_t) + 16;
     const size_t merge_lds = (size_t)merge_pow2 * sizeof(uint64_t);
     if (scan_lds > 64 * 1024) {   // above the default dynamic LDS window
         const void *fn = M == 16 ? reinterpret_cast<const void *>(&scan_kernel<16>)
@@ -363,15 +363,15 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
 
         if (M == 16)
             scan_kernel<16><<<dim3((unsigned)(n * nsplit)), dim3(SCAN_BLOCK), scan_lds, st>>>(
-                ix->blocks, ix->ids, ix->const_table, desc, S, lut, k, nsplit, partial);
+                ix->blocks, ix->const_table, desc, S, lut, k, nsplit, partial);
         else
             scan_kernel<8><<<dim3((unsigned)(n * nsplit)), dim3(SCAN_BLOCK), scan_lds, st>>>(
-                ix->blocks, ix->ids, ix->const_table, desc, S, lut, k, nsplit, partial);
+                ix->blocks, ix->const_table, desc, S, lut, k, nsplit, partial);
         LAUNCHCHK("scan_kernel");
         if ((rc = mark(6))) return rc;
 
         merge_kernel<256><<<dim3((unsigned)n), dim3(256), merge_lds, st>>>(
-            partial, merge_n, merge_pow2, k, out_ids + q0 * k, out_dists + q0 * k);
+            partial, ix->ids, merge_n, merge_pow2, k, out_ids + q0 * k, out_dists + q0 * k);
         LAUNCHCHK("merge_kernel");
         if ((rc = mark(7))) return rc;
         if (ix->profile) ix->launches++;
@@ -530,5 +530,19 @@ extern "C" int ivf_alpha_stats(const float *centroids, int64_t K, int D, const i
     alpha_stats_kernel<<<dim3((unsigned)n), dim3(64), (size_t)D * sizeof(float), st>>>(
         x, n, D, L, region, centroids, nbr, num, den);
     LAUNCHCHK("alpha_stats_kernel");
+    return IVF_OK;
+}
+
+extern "C" int ivf_copy_bytes(void *dst, const void *src, int64_t nbytes, void *hip_stream)
+{
+    if (!dst || !src || nbytes < 0 || nbytes % 16 || !aligned16(dst) || !aligned16(src))
+        return fail(IVF_EINVAL, "ivf_copy_bytes needs 16-byte aligned pointers and a multiple of 16 bytes");
+    if (nbytes == 0) return IVF_OK;
+    const int64_t n16 = nbytes / 16;
+    int64_t grid = (n16 + 255) / 256;
+    if (grid > 256 * 32) grid = 256 * 32;
+    copy_bytes_kernel<<<dim3((unsigned)grid), dim3(256), 0, static_cast<hipStream_t>(hip_stream)>>>(
+        static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n16);
+    LAUNCHCHK("copy_bytes_kernel");
     return IVF_OK;
 }

@@ -51,4 +51,13 @@ __global__ __launch_bounds__(256) void repack_kernel(
     }
 }
 
+// plain streaming copy of n16 16-byte words (reference point for HBM counters and timings)
+__global__ __launch_bounds__(256) void copy_bytes_kernel(const uint4 *__restrict__ src,
+                                                         uint4 *__restrict__ dst, int64_t n16)
+{
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
 }  // namespace ivf

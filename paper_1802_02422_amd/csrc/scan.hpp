@@ -14,42 +14,64 @@ constexpr int SCAN_WAVES = SCAN_BLOCK / WAVE;
 
 __host__ __device__ inline int pool_capacity(int k)
 {
-    int cap = 128;
+    int cap = 256;
     while (cap < 2 * k) cap <<= 1;
     return cap;
 }
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 template <int M> struct CodeWord;
-template <> struct CodeWord<16> { typedef uint4 type; };
-template <> struct CodeWord<8> { typedef uint2 type; };
+template <> struct CodeWord<16> { typedef u32x4 type; };
+template <> struct CodeWord<8> { typedef u32x2 type; };
+
+// 4 * (byte B of w) in one VALU instruction (SDWA byte select feeding a shift);
+// `two` is a register holding 2.
+template <int B>
+__device__ __forceinline__ uint32_t byte_x4(uint32_t w, uint32_t two)
+{
+    uint32_t r;
+    if (B == 0) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(two), "v"(w));
+    if (B == 1) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(two), "v"(w));
+    if (B == 2) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(two), "v"(w));
+    if (B == 3) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(two), "v"(w));
+    return r;
+}
+
+// acc + sum_m T[m][byte m of the word] for the four bytes of one code word,
+// sub-quantisers m0 .. m0+3; T is the table base as a byte pointer.
+template <int M0>
+__device__ __forceinline__ float adc_word(uint32_t w, const char *T, float acc, uint32_t two)
+{
+    acc += *reinterpret_cast<const float *>(T + (M0 + 0) * 1024 + byte_x4<0>(w, two));
+    acc += *reinterpret_cast<const float *>(T + (M0 + 1) * 1024 + byte_x4<1>(w, two));
+    acc += *reinterpret_cast<const float *>(T + (M0 + 2) * 1024 + byte_x4<2>(w, two));
+    acc += *reinterpret_cast<const float *>(T + (M0 + 3) * 1024 + byte_x4<3>(w, two));
+    return acc;
+}
 
 template <int M>
-__device__ __forceinline__ float adc_sum(const typename CodeWord<M>::type &c, const float *T, float acc);
+__device__ __forceinline__ float adc_sum(const typename CodeWord<M>::type &c, const char *T, float acc, uint32_t two);
 
 template <>
-__device__ __forceinline__ float adc_sum<16>(const uint4 &c, const float *T, float acc)
+__device__ __forceinline__ float adc_sum<16>(const u32x4 &c, const char *T, float acc, uint32_t two)
 {
-    const uint32_t w[4] = {c.x, c.y, c.z, c.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) acc += T[(4 * i + b) * 256 + ((w[i] >> (8 * b)) & 255u)];
-    return acc;
+    acc = adc_word<0>(c.x, T, acc, two);
+    acc = adc_word<4>(c.y, T, acc, two);
+    acc = adc_word<8>(c.z, T, acc, two);
+    return adc_word<12>(c.w, T, acc, two);
 }
 
 template <>
-__device__ __forceinline__ float adc_sum<8>(const uint2 &c, const float *T, float acc)
+__device__ __forceinline__ float adc_sum<8>(const u32x2 &c, const char *T, float acc, uint32_t two)
 {
-    const uint32_t w[2] = {c.x, c.y};
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) acc += T[(4 * i + b) * 256 + ((w[i] >> (8 * b)) & 255u)];
-    return acc;
+    acc = adc_word<0>(c.x, T, acc, two);
+    return adc_word<4>(c.y, T, acc, two);
 }
 
-// Sort the wave's pool, keep its k best, return the new admission threshold.
-__device__ __forceinline__ float wave_pool_compact(uint64_t *pool, int cap, int &pool_n, int k)
+// Sort the wave's pool, keep its k best, return the new admission threshold
+// (any pool capacity; used when the pool does not fit the register path below).
+__device__ __forceinline__ float wave_pool_sort(uint64_t *pool, int cap, int &pool_n, int k)
 {
     const int lane = threadIdx.x & (WAVE - 1);
     for (int i = pool_n + lane; i < cap; i += WAVE) pool[i] = EMPTY_KEY;
@@ -60,78 +82,238 @@ __device__ __forceinline__ float wave_pool_compact(uint64_t *pool, int cap, int 
     return theta;
 }
 
+// The same for a pool of 256 keys without sorting: four keys per lane in
+// registers, the k-th smallest found by an MSB-first bitwise search with
+// wave-wide population counts (first over the distance word; over the low word
+// only when distances tie at the boundary), survivors written back compacted
+// (unordered).  Exactly min(pool_n, k) keys survive.
+__device__ __forceinline__ float wave_pool_select256(uint64_t *pool, int &pool_n, int k)
+{
+    if (pool_n <= k) return INFINITY;
+    const int lane = threadIdx.x & (WAVE - 1);
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int idx = lane + WAVE * j;
+        const uint64_t key = idx < pool_n ? pool[idx] : EMPTY_KEY;
+        hi[j] = (uint32_t)(key >> 32);
+        lo[j] = (uint32_t)key;
+    }
+    uint32_t pref = 0;
+    int rem = k;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t mask = ~((1u << bit) - 1u);
+        int cnt = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) cnt += __popcll(__ballot((hi[j] & mask) == pref));
+        if (rem > cnt) { rem -= cnt; pref |= 1u << bit; }
+    }
+    int ceq = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) ceq += __popcll(__ballot(hi[j] == pref));
+    uint32_t lo_thr = 0xFFFFFFFFu;
+    if (ceq > rem) {   // equal distances straddle rank k: keep the rem lowest low words
+        uint32_t p2 = 0;
+        int r2 = rem;
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t mask = ~((1u << bit) - 1u);
+            int cnt = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) cnt += __popcll(__ballot(hi[j] == pref && (lo[j] & mask) == p2));
+            if (r2 > cnt) { r2 -= cnt; p2 |= 1u << bit; }
+        }
+        lo_thr = p2;
+    }
+    wave_sync();
+    int base = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const bool keep = hi[j] < pref || (hi[j] == pref && lo[j] <= lo_thr);
+        const uint64_t m = __ballot(keep);
+        if (keep) pool[base + __popcll(m & ((1ull << lane) - 1ull))] = ((uint64_t)hi[j] << 32) | lo[j];
+        base += __popcll(m);
+    }
+    pool_n = base;
+    wave_sync();
+    return key_float(pref);
+}
+
+__device__ __forceinline__ float wave_pool_compact(uint64_t *pool, int cap, int &pool_n, int k)
+{
+    return cap == 256 ? wave_pool_select256(pool, pool_n, k) : wave_pool_sort(pool, cap, pool_n, k);
+}
+
+constexpr int SCAN_U = 4;                     // 64-record steps per chunk
+constexpr int SCAN_CHUNK = WAVE * SCAN_U;     // records a wavefront has in flight per chunk
+
+// Per-wavefront LDS staging of a batch of 64 descriptors.
+struct WaveStage {
+    uint4 a[WAVE];              // address of the codes (lo, hi), address of the constant bytes (lo, hi)
+    uint4 b[WAVE];              // first flattened record index, len, base (bits), pos0
+    uint8_t mark[SCAN_CHUNK];   // 1 + lane of the descriptor whose first record sits here, else 0
+};
+static_assert(SCAN_CHUNK % 16 == 0 && sizeof(WaveStage) % 16 == 0, "stage arrays must stay 16-byte aligned");
+
+template <int M>
+struct ChunkRegs {
+    typename CodeWord<M>::type code[SCAN_U];
+    uint32_t cb[SCAN_U];        // constant byte
+    float base[SCAN_U];
+    uint32_t own[SCAN_U];       // owning descriptor (lane of the batch), 0xFFFFFFFF = no record
+    uint32_t c[SCAN_U];         // record index inside its subregion
+};
+
+// Find the owner of every record of the chunk starting at flattened index t0
+// and issue its two loads.
+template <int M>
+__device__ __forceinline__ void scan_issue(ChunkRegs<M> &r, WaveStage &st, uint32_t t0, uint32_t T,
+                                           uint32_t len, uint32_t pre, uint32_t &carry)
+{
+    typedef typename CodeWord<M>::type code_t;
+    const int lane = threadIdx.x & (WAVE - 1);
+#pragma unroll
+    for (int i = lane; i < SCAN_CHUNK / 4; i += WAVE) reinterpret_cast<uint32_t *>(st.mark)[i] = 0u;
+    wave_sync();
+    if (len > 0 && pre >= t0 && pre - t0 < (uint32_t)SCAN_CHUNK) st.mark[pre - t0] = (uint8_t)(lane + 1);
+    wave_sync();
+    uint32_t sc[SCAN_U], tot[SCAN_U];
+#pragma unroll
+    for (int u = 0; u < SCAN_U; ++u) sc[u] = (uint32_t)st.mark[WAVE * u + lane];
+#pragma unroll
+    for (int u = 0; u < SCAN_U; ++u) sc[u] = wave_inclusive_max_scan(sc[u]);   // four independent chains
+#pragma unroll
+    for (int u = 0; u < SCAN_U; ++u) tot[u] = (uint32_t)__builtin_amdgcn_readlane((int)sc[u], WAVE - 1);
+#pragma unroll
+    for (int u = 0; u < SCAN_U; ++u) {
+        const uint32_t t = t0 + WAVE * u + lane;
+        const uint32_t o = sc[u] > carry ? sc[u] : carry;
+        carry = tot[u] > carry ? tot[u] : carry;
+        bool act = t < T && o > 0;
+        const uint32_t oi = act ? o - 1 : 0;
+        const uint4 db = st.b[oi];
+        const uint32_t c = t - db.x;
+        act = act && c < db.y;                     // never read outside the owner's block
+        r.own[u] = act ? oi : 0xFFFFFFFFu;
+        r.c[u] = c;
+        r.base[u] = __uint_as_float(db.z);
+        r.cb[u] = 0;
+        if (act) {
+            const uint4 da = st.a[oi];
+            typedef const __attribute__((address_space(1))) code_t *gcode_p;   // global, not flat, loads
+            typedef const __attribute__((address_space(1))) uint8_t *gbyte_p;
+            const uint64_t pc = ((uint64_t)da.y << 32) | da.x, pb = ((uint64_t)da.w << 32) | da.z;
+            r.code[u] = *reinterpret_cast<gcode_p>(pc + (uint64_t)c * M);
+            r.cb[u] = *reinterpret_cast<gbyte_p>(pb + c);
+        }
+    }
+}
+
 // Grid: nq * nsplit workgroups; workgroup (q, split) scans an equal share of
-// the query's S descriptors.  A group of 16 lanes walks one subregion, one
-// record per lane per step (a 16-byte code load at M = 16), looks the M bytes
-// up in the query's table held in LDS, adds the subregion base and the
-// dequantised constant byte, and offers the estimate to its wavefront's pool.
-// Output: per (q, split, wave) the k best keys (distance, id), ascending,
-// padded with EMPTY_KEY.
+// the query's S descriptors, each wavefront batches of 64 of them.  The
+// records of a batch are flattened: a prefix sum of the lengths numbers them,
+// every lane takes record t = t0 + 64u + lane of the current chunk, and finds
+// the owning descriptor from head marks in LDS by a running maximum across
+// the lanes (DPP).  All lanes are busy whatever the subregion lengths, a
+// 16-byte code is one 128-bit load, and the loads of the next chunk are issued
+// before the table lookups of the current one, so each wavefront keeps two
+// chunks (about 8 KB) in flight.  The M bytes index the query's table in LDS;
+// the estimate (Eq. (6)) is offered to the wavefront's top-k pool, keyed by
+// (distance, grouped position): ids are not touched here, the final k-select
+// reads them for the survivors and orders by (distance, id).  The admission
+// threshold is shared by the workgroup's wavefronts: once any of them holds k
+// candidates, nothing above its k-th distance can be a result.
+// Output: per (q, split, wave) the k best keys (distance, position), in no
+// particular order, padded with EMPTY_KEY.
 template <int M>
 __global__ __launch_bounds__(SCAN_BLOCK) void scan_kernel(
-    const uint8_t *__restrict__ blocks, const int32_t *__restrict__ ids,
-    const float *__restrict__ const_table, const SubDesc *__restrict__ desc, int S,
-    const float *__restrict__ lut, int k, int nsplit, uint64_t *__restrict__ partial)
+    const uint8_t *__restrict__ blocks, const float *__restrict__ const_table,
+    const SubDesc *__restrict__ desc, int S, const float *__restrict__ lut, int k, int nsplit,
+    uint64_t *__restrict__ partial)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    float *T = reinterpret_cast<float *>(smem);                 // M*256
-    float *nt = T + M * 256;                                    // 256
-    uint64_t *pools = reinterpret_cast<uint64_t *>(nt + 256);   // SCAN_WAVES * cap
-    typedef typename CodeWord<M>::type code_t;
+    float *T = reinterpret_cast<float *>(smem);                            // M*256
+    float *nt = T + M * 256;                                               // 256
+    WaveStage *stages = reinterpret_cast<WaveStage *>(nt + 256);           // SCAN_WAVES
+    uint64_t *pools = reinterpret_cast<uint64_t *>(stages + SCAN_WAVES);   // SCAN_WAVES * cap
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int64_t q = blockIdx.x / nsplit;
     const int split = blockIdx.x % nsplit;
     const int cap = pool_capacity(k);
     uint64_t *pool = pools + wave * cap;
+    uint32_t &wg_theta_key = *reinterpret_cast<uint32_t *>(pools + SCAN_WAVES * cap);   // table stays at LDS address 0
+    WaveStage &st = stages[wave];
+    const char *Tb = reinterpret_cast<const char *>(T);
+    uint32_t two = 2;
+    asm volatile("" : "+v"(two));   // keep the shift amount in a vector register
 
     {
         const float4 *src = reinterpret_cast<const float4 *>(lut + q * (int64_t)(M * 256));
         float4 *dst = reinterpret_cast<float4 *>(T);
         for (int i = tid; i < M * 64; i += SCAN_BLOCK) dst[i] = src[i];
         nt[tid] = const_table[tid];
+        if (tid == 0) wg_theta_key = float_key(INFINITY);
     }
     __syncthreads();
 
     const int d_begin = (int)(((int64_t)S * split) / nsplit);
     const int d_end = (int)(((int64_t)S * (split + 1)) / nsplit);
     const SubDesc *qd = desc + q * S;
-    const int g = lane >> 4, c_lane = lane & 15;
 
     int pool_n = 0;
     float theta = INFINITY;
 
-    for (int d0 = d_begin + wave * 4; d0 < d_end; d0 += SCAN_WAVES * 4) {
-        const int d = d0 + g;
-        SubDesc sd;
-        sd.blk = 0; sd.pos0 = 0; sd.len = 0; sd.base = 0.f;
-        if (d < d_end) sd = qd[d];
-        uint32_t maxlen = sd.len;
-#pragma unroll
-        for (int o = 32; o >= 16; o >>= 1) {
-            uint32_t t = __shfl_xor(maxlen, o, WAVE);
-            maxlen = t > maxlen ? t : maxlen;
+    SubDesc sd_next;
+    sd_next.blk = 0; sd_next.pos0 = 0; sd_next.len = 0; sd_next.base = 0.f;
+    {
+        const int d = d_begin + wave * WAVE + lane;
+        if (d < d_end) sd_next = qd[d];
+    }
+    for (int b0 = d_begin + wave * WAVE; b0 < d_end; b0 += SCAN_WAVES * WAVE) {
+        const SubDesc sd = sd_next;
+        {   // prefetch the next batch's descriptors
+            const int d = b0 + SCAN_WAVES * WAVE + lane;
+            sd_next.blk = 0; sd_next.pos0 = 0; sd_next.len = 0; sd_next.base = 0.f;
+            if (d < d_end) sd_next = qd[d];
         }
-        const uint8_t *blk = blocks + (uint64_t)sd.blk * 64u;
-        for (uint32_t c0 = 0; c0 < maxlen; c0 += 16) {
-            const uint32_t c = c0 + c_lane;
-            const bool active = c < sd.len;
-            float dist = INFINITY;
-            if (active) {
-                code_t code = *reinterpret_cast<const code_t *>(blk + (uint64_t)c * M);
-                uint32_t cb = blk[(uint64_t)sd.len * M + c];
-                dist = adc_sum<M>(code, T, sd.base + nt[cb]);
-            }
-            const bool pass = active && dist <= theta;
-            const uint64_t mask = __ballot(pass);
-            if (mask) {
-                if (pass) {
-                    int slot = pool_n + __popcll(mask & ((1ull << lane) - 1ull));
-                    pool[slot] = dist_id_key(dist, ids[sd.pos0 + c]);
+        const uint32_t len = sd.len;
+        const uint32_t inc = wave_inclusive_scan(len);
+        const uint32_t pre = inc - len;
+        const uint32_t Tn = (uint32_t)__builtin_amdgcn_readlane((int)inc, WAVE - 1);
+        wave_sync();
+        {
+            const uint64_t pc = reinterpret_cast<uint64_t>(blocks) + (uint64_t)sd.blk * 64u;
+            const uint64_t pb = pc + (uint64_t)len * M;
+            st.a[lane] = make_uint4((uint32_t)pc, (uint32_t)(pc >> 32), (uint32_t)pb, (uint32_t)(pb >> 32));
+            st.b[lane] = make_uint4(pre, len, __float_as_uint(sd.base), sd.pos0);
+        }
+        uint32_t carry = 0;
+        ChunkRegs<M> cur, nxt;
+        if (Tn > 0) scan_issue<M>(cur, st, 0u, Tn, len, pre, carry);
+        for (uint32_t t0 = 0; t0 < Tn; t0 += SCAN_CHUNK) {
+            const bool more = t0 + SCAN_CHUNK < Tn;
+            if (more) scan_issue<M>(nxt, st, t0 + SCAN_CHUNK, Tn, len, pre, carry);
+            theta = fminf(theta, key_float(wg_theta_key));
+#pragma unroll
+            for (int u = 0; u < SCAN_U; ++u) {
+                const bool active = cur.own[u] != 0xFFFFFFFFu;
+                float dist = INFINITY;
+                if (active) dist = adc_sum<M>(cur.code[u], Tb, cur.base[u] + nt[cur.cb[u]], two);
+                const bool pass = active && dist <= theta;
+                const uint64_t mask = __ballot(pass);
+                if (mask) {
+                    if (pass) {
+                        int slot = pool_n + __popcll(mask & ((1ull << lane) - 1ull));
+                        pool[slot] = ((uint64_t)float_key(dist) << 32) | (st.b[cur.own[u]].w + cur.c[u]);
+                    }
+                    pool_n += __popcll(mask);
+                    if (pool_n > cap - WAVE) {
+                        theta = wave_pool_compact(pool, cap, pool_n, k);
+                        if (lane == 0) atomicMin(&wg_theta_key, float_key(theta));
+                    }
                 }
-                pool_n += __popcll(mask);
-                if (pool_n > cap - WAVE) theta = wave_pool_compact(pool, cap, pool_n, k);
             }
+            if (more) cur = nxt;
         }
     }
     wave_pool_compact(pool, cap, pool_n, k);
@@ -139,17 +321,23 @@ __global__ __launch_bounds__(SCAN_BLOCK) void scan_kernel(
     for (int i = lane; i < k; i += WAVE) out[i] = i < pool_n ? pool[i] : EMPTY_KEY;
 }
 
-// Final k-select: sort the n_lists * k partial keys of a query and write the k
-// best as (id, distance); empty slots become (-1, +inf).
+// Final k-select: replace the position of every partial key by the point's id,
+// sort the n_lists * k keys (distance, id) of a query and write the k best;
+// empty slots become (-1, +inf).
 template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void merge_kernel(const uint64_t *__restrict__ partial, int n_in,
+__global__ __launch_bounds__(BLOCK) void merge_kernel(const uint64_t *__restrict__ partial,
+                                                      const int32_t *__restrict__ ids, int n_in,
                                                       int n_pow2, int k, int32_t *__restrict__ out_ids,
                                                       float *__restrict__ out_dists)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint64_t *a = reinterpret_cast<uint64_t *>(smem);
     const int64_t q = blockIdx.x;
-    for (int i = threadIdx.x; i < n_pow2; i += BLOCK) a[i] = i < n_in ? partial[q * n_in + i] : EMPTY_KEY;
+    for (int i = threadIdx.x; i < n_pow2; i += BLOCK) {
+        uint64_t key = i < n_in ? partial[q * n_in + i] : EMPTY_KEY;
+        if (key != EMPTY_KEY) key = (key & 0xFFFFFFFF00000000ull) | (uint32_t)ids[(uint32_t)key];
+        a[i] = key;
+    }
     block_bitonic_sort<BLOCK>(a, n_pow2);
     for (int i = threadIdx.x; i < k; i += BLOCK) {
         uint64_t key = i < n_pow2 ? a[i] : EMPTY_KEY;

@@ -49,6 +49,29 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
     return v;
 }
 
+// DPP move with 0 for lanes that have no source (shifted out of their row of 16,
+// or in a row excluded by ROW_MASK).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+
+// Inclusive running maximum over the 64 lanes in 6 DPP steps, no LDS:
+// row_shr 1/2/4/8 scan each row of 16, row_bcast15 carries rows 0,2 into rows
+// 1,3, row_bcast31 carries lane 31 into rows 2,3.
+__device__ __forceinline__ uint32_t wave_inclusive_max_scan(uint32_t v)
+{
+    uint32_t t;
+    t = dpp_or_zero<0x111, 0xf>(v); v = t > v ? t : v;
+    t = dpp_or_zero<0x112, 0xf>(v); v = t > v ? t : v;
+    t = dpp_or_zero<0x114, 0xf>(v); v = t > v ? t : v;
+    t = dpp_or_zero<0x118, 0xf>(v); v = t > v ? t : v;
+    t = dpp_or_zero<0x142, 0xa>(v); v = t > v ? t : v;
+    t = dpp_or_zero<0x143, 0xc>(v); v = t > v ? t : v;
+    return v;
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
