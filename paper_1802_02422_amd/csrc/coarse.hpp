@@ -70,15 +70,18 @@ __device__ __forceinline__ void gemm_tile(const float *__restrict__ Q, int64_t n
                 a[i] = *reinterpret_cast<const float4 *>(&As[(wq + i * 32 + l32) * GLD + h * 16 + s4 * 4]);
                 b[i] = *reinterpret_cast<const float4 *>(&Bs[(wc + i * 32 + l32) * GLD + h * 16 + s4 * 4]);
             }
+            // the four accumulators are independent: cycle through them so that no MFMA
+            // waits for the one issued just before it
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int e = 0; e < 4; ++e)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b[j].x, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b[j].y, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b[j].z, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b[j].w, acc[i][j], 0, 0, 0);
-                }
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const float av = e == 0 ? a[i].x : e == 1 ? a[i].y : e == 2 ? a[i].z : a[i].w;
+                        const float bv = e == 0 ? b[j].x : e == 1 ? b[j].y : e == 2 ? b[j].z : b[j].w;
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                    }
         }
         __syncthreads();
     }
@@ -126,9 +129,14 @@ __global__ __launch_bounds__(256) void coarse_gemm_kernel(
                     if (row < nq) Dt[row * K + col[j]] = d;
                     m = fminf(m, d);
                 }
-#pragma unroll
-            for (int o = 16; o > 0; o >>= 1) m = fminf(m, __shfl_xor(m, o, WAVE));
-            if (l32 == 0 && row < nq && blk < nb) bm[row * nb + blk] = m;
+            // minimum over the 32 lanes that share the row: rotate-and-min inside each row of
+            // 16 (DPP row_ror 8/4/2/1), then lane 15 of rows 0/2 into rows 1/3 (row_bcast15)
+            m = fminf(m, dpp_float<0x128, 0xf>(m));
+            m = fminf(m, dpp_float<0x124, 0xf>(m));
+            m = fminf(m, dpp_float<0x122, 0xf>(m));
+            m = fminf(m, dpp_float<0x121, 0xf>(m));
+            m = fminf(m, dpp_float<0x142, 0xa>(m, INFINITY));
+            if (l32 == 16 && row < nq && blk < nb) bm[row * nb + blk] = m;
         }
 }
 

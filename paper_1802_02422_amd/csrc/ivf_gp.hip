@@ -302,10 +302,9 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
     if ((rc = ensure(ix->lut, (size_t)tile * M * 256 * sizeof(float)))) return rc;
     if ((rc = ensure(ix->partial, (size_t)tile * merge_n * sizeof(uint64_t)))) return rc;
 
-    const size_t scan_lds = (size_t)(M * 256 + 256) * sizeof(float) + SCAN_WAVES * sizeof(WaveStage) +
-                            (size_t)SCAN_WAVES * pool_capacity(k) * sizeof(uint64_t) + 16;
+    const size_t scan_lds = (size_t)SCAN_WAVES * pool_capacity(k) * sizeof(uint64_t);   // dynamic part: the pools
     const size_t merge_lds = (size_t)merge_pow2 * sizeof(uint64_t);
-    if (scan_lds > 64 * 1024) {   // above the default dynamic LDS window
+    if (scan_lds > 32 * 1024) {   // dynamic + static LDS above the default 64 KB window
         const void *fn = M == 16 ? reinterpret_cast<const void *>(&scan_kernel<16>)
                                  : reinterpret_cast<const void *>(&scan_kernel<8>);
         HIPCHK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds));

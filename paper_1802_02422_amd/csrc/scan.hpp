@@ -230,18 +230,20 @@ __global__ __launch_bounds__(SCAN_BLOCK) void scan_kernel(
     const SubDesc *__restrict__ desc, int S, const float *__restrict__ lut, int k, int nsplit,
     uint64_t *__restrict__ partial)
 {
+    // The table sits in static LDS so that its address is a compile-time constant and every
+    // lookup is one ds_read with an immediate offset; only the pools are sized at launch.
+    __shared__ __attribute__((aligned(16))) float T[M * 256];
+    __shared__ float nt[256];
+    __shared__ WaveStage stages[SCAN_WAVES];
+    __shared__ uint32_t wg_theta_key;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    float *T = reinterpret_cast<float *>(smem);                            // M*256
-    float *nt = T + M * 256;                                               // 256
-    WaveStage *stages = reinterpret_cast<WaveStage *>(nt + 256);           // SCAN_WAVES
-    uint64_t *pools = reinterpret_cast<uint64_t *>(stages + SCAN_WAVES);   // SCAN_WAVES * cap
+    uint64_t *pools = reinterpret_cast<uint64_t *>(smem);                  // SCAN_WAVES * cap
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int64_t q = blockIdx.x / nsplit;
     const int split = blockIdx.x % nsplit;
     const int cap = pool_capacity(k);
     uint64_t *pool = pools + wave * cap;
-    uint32_t &wg_theta_key = *reinterpret_cast<uint32_t *>(pools + SCAN_WAVES * cap);   // table stays at LDS address 0
     WaveStage &st = stages[wave];
     const char *Tb = reinterpret_cast<const char *>(T);
     uint32_t two = 2;
@@ -288,11 +290,9 @@ __global__ __launch_bounds__(SCAN_BLOCK) void scan_kernel(
             st.b[lane] = make_uint4(pre, len, __float_as_uint(sd.base), sd.pos0);
         }
         uint32_t carry = 0;
-        ChunkRegs<M> cur, nxt;
-        if (Tn > 0) scan_issue<M>(cur, st, 0u, Tn, len, pre, carry);
-        for (uint32_t t0 = 0; t0 < Tn; t0 += SCAN_CHUNK) {
-            const bool more = t0 + SCAN_CHUNK < Tn;
-            if (more) scan_issue<M>(nxt, st, t0 + SCAN_CHUNK, Tn, len, pre, carry);
+        // two register sets used alternately: the loads of chunk c+1 are in flight while chunk c is consumed
+        ChunkRegs<M> ra, rb;
+        auto consume = [&](ChunkRegs<M> &cur) {
             theta = fminf(theta, key_float(wg_theta_key));
 #pragma unroll
             for (int u = 0; u < SCAN_U; ++u) {
@@ -313,7 +313,15 @@ __global__ __launch_bounds__(SCAN_BLOCK) void scan_kernel(
                     }
                 }
             }
-            if (more) cur = nxt;
+        };
+        if (Tn > 0) scan_issue<M>(ra, st, 0u, Tn, len, pre, carry);
+        for (uint32_t t0 = 0; t0 < Tn; t0 += 2 * SCAN_CHUNK) {
+            const bool more1 = t0 + SCAN_CHUNK < Tn;
+            if (more1) scan_issue<M>(rb, st, t0 + SCAN_CHUNK, Tn, len, pre, carry);
+            consume(ra);
+            if (!more1) break;
+            if (t0 + 2 * SCAN_CHUNK < Tn) scan_issue<M>(ra, st, t0 + 2 * SCAN_CHUNK, Tn, len, pre, carry);
+            consume(rb);
         }
     }
     wave_pool_compact(pool, cap, pool_n, k);

@@ -57,6 +57,14 @@ __device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v)
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
 }
 
+// DPP move of a float; lanes without a source (row excluded by ROW_MASK) get `fill`.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_float(float v, float fill = 0.f)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(fill), __float_as_int(v), CTRL,
+                                                      ROW_MASK, 0xf, false));
+}
+
 // Inclusive running maximum over the 64 lanes in 6 DPP steps, no LDS:
 // row_shr 1/2/4/8 scan each row of 16, row_bcast15 carries rows 0,2 into rows
 // 1,3, row_bcast31 carries lane 31 into rows 2,3.
