@@ -32,8 +32,11 @@ constexpr int GLD = GKC + 4;   // LDS row stride in floats (keeps 16-byte alignm
 // wavefront owns a 64x64 quadrant as 2x2 v_mfma_f32_32x32x2f32 accumulators.
 // Within a 32-dim stage lane half h feeds dims [16h, 16h+16) to both operands,
 // so one ds_read_b128 serves four MFMA steps (the order of the k-summation is
-// free).  Accumulator element v of lane l is row 8*(v/4) + 4*(l/32) + v%4,
-// column l%32 of its 32x32 block.
+// free).  The centroids are the MFMA's row operand and the queries its column
+// operand: in acc[i][j], lane l holds query (column) wq + 32i + l%32 and element
+// v is centroid (row) wc + 32j + 8*(v/4) + 4*(l/32) + v%4, i.e. four groups of
+// four consecutive centroids, which the epilogues store as 128-bit words and
+// reduce without leaving the lane.
 __device__ __forceinline__ void gemm_tile(const float *__restrict__ Q, int64_t nq, int64_t q0,
                                           const float *__restrict__ C, int64_t K, int64_t c0, int D,
                                           float *As, float *Bs, floatx16 (&acc)[2][2])
@@ -48,20 +51,33 @@ __device__ __forceinline__ void gemm_tile(const float *__restrict__ Q, int64_t n
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+    // the global loads of stage s+1 are issued before the MFMA block of stage s and
+    // land in registers while it runs
+    float4 pa[4], pb[4];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            int idx = tid + it * 256;
+            int row = idx >> 3, c4 = (idx & 7) * 4;
+            pa[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            pb[it] = pa[it];
+            if (k0 + c4 < D) {
+                if (q0 + row < nq) pa[it] = *reinterpret_cast<const float4 *>(Q + (q0 + row) * D + k0 + c4);
+                if (c0 + row < K) pb[it] = *reinterpret_cast<const float4 *>(C + (c0 + row) * D + k0 + c4);
+            }
+        }
+    };
+    fetch(0);
     for (int k0 = 0; k0 < D; k0 += GKC) {
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             int idx = tid + it * 256;
             int row = idx >> 3, c4 = (idx & 7) * 4;
-            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
-            if (k0 + c4 < D) {
-                if (q0 + row < nq) a = *reinterpret_cast<const float4 *>(Q + (q0 + row) * D + k0 + c4);
-                if (c0 + row < K) b = *reinterpret_cast<const float4 *>(C + (c0 + row) * D + k0 + c4);
-            }
-            *reinterpret_cast<float4 *>(&As[row * GLD + c4]) = a;
-            *reinterpret_cast<float4 *>(&Bs[row * GLD + c4]) = b;
+            *reinterpret_cast<float4 *>(&As[row * GLD + c4]) = pa[it];
+            *reinterpret_cast<float4 *>(&Bs[row * GLD + c4]) = pb[it];
         }
         __syncthreads();
+        if (k0 + GKC < D) fetch(k0 + GKC);
 #pragma unroll
         for (int s4 = 0; s4 < 4; ++s4) {
             float4 a[2], b[2];
@@ -80,7 +96,7 @@ __device__ __forceinline__ void gemm_tile(const float *__restrict__ Q, int64_t n
                     for (int j = 0; j < 2; ++j) {
                         const float av = e == 0 ? a[i].x : e == 1 ? a[i].y : e == 2 ? a[i].z : a[i].w;
                         const float bv = e == 0 ? b[j].x : e == 1 ? b[j].y : e == 2 ? b[j].z : b[j].w;
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av, acc[i][j], 0, 0, 0);
                     }
         }
         __syncthreads();
@@ -88,11 +104,25 @@ __device__ __forceinline__ void gemm_tile(const float *__restrict__ Q, int64_t n
 }
 
 constexpr int BMW = 64;   // centroids per block minimum
+constexpr int N_XCD = 8;  // workgroups are dealt round-robin to the 8 XCDs, each with its own L2
+
+// Tile of workgroup b: XCD x = b % 8 owns the query tiles x, x+8, ... (a few hundred KB that
+// stay in its L2) and sweeps the centroid tiles in order, so every XCD streams the centroid
+// matrix once and the eight of them work on the same centroid tile at about the same time.
+__device__ __forceinline__ bool tile_of_block(int64_t b, int tiles_q, int64_t &q0, int64_t &c0)
+{
+    const int tq_per = (tiles_q + N_XCD - 1) / N_XCD;
+    const int xcd = (int)(b % N_XCD);
+    const int64_t local = b / N_XCD;
+    const int tq = (int)(local % tq_per) * N_XCD + xcd;
+    q0 = (int64_t)tq * GT;
+    c0 = (local / tq_per) * GT;
+    return tq < tiles_q;
+}
 
 // Dt[q][j] = max(0, qn[q] + cn[j] - 2 <Q[q], C[j]>), and bm[q][b] = the minimum
-// of Dt[q][64b .. 64b+63] (each wavefront's 64-column quadrant gives one block
-// minimum per row).  Tiles are numbered centroid-tile-major so that the query
-// tiles (small, L2 resident) are swept against one centroid tile after the other.
+// of Dt[q][64b .. 64b+63] (each wavefront's 64-centroid quadrant gives one block
+// minimum per query).  The grid has 8 * ceil(tiles_q / 8) * tiles_c workgroups.
 __global__ __launch_bounds__(256) void coarse_gemm_kernel(
     const float *__restrict__ Q, const float *__restrict__ qn, int64_t nq,
     const float *__restrict__ C, const float *__restrict__ cn, int64_t K, int D,
@@ -100,50 +130,63 @@ __global__ __launch_bounds__(256) void coarse_gemm_kernel(
 {
     __shared__ __attribute__((aligned(16))) float As[GT * GLD];
     __shared__ __attribute__((aligned(16))) float Bs[GT * GLD];
+    __shared__ __attribute__((aligned(16))) float cns[GT];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t tile = blockIdx.x;
-    const int64_t q0 = (tile % tiles_q) * GT, c0 = (tile / tiles_q) * GT;
+    int64_t q0, c0;
+    if (!tile_of_block(blockIdx.x, tiles_q, q0, c0)) return;
     const int wq = (wave >> 1) * 64, wc = (wave & 1) * 64;
     const int l32 = lane & 31, h = lane >> 5;
+    if (threadIdx.x < GT) cns[threadIdx.x] = c0 + threadIdx.x < K ? cn[c0 + threadIdx.x] : 0.f;
     floatx16 acc[2][2];
-    gemm_tile(Q, nq, q0, C, K, c0, D, As, Bs, acc);
-    float cnj[2];
-    int64_t col[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        col[j] = c0 + wc + j * 32 + l32;
-        cnj[j] = col[j] < K ? cn[col[j]] : 0.f;
-    }
+    gemm_tile(Q, nq, q0, C, K, c0, D, As, Bs, acc);   // ends with a barrier: cns is visible
+    const bool vec = (K & 3) == 0;
     const int64_t blk = (c0 + wc) / BMW;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) {
+        const int64_t q = q0 + wq + i * 32 + l32;
+        const float qr = q < nq ? qn[q] : 0.f;
+        float *rowp = Dt + q * K;
+        float m = INFINITY;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            int64_t row = q0 + wq + i * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            float qr = row < nq ? qn[row] : 0.f;
-            float m = INFINITY;
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                if (col[j] < K) {
-                    float d = fmaxf(fmaf(-2.f, acc[i][j][v], qr + cnj[j]), 0.f);
-                    if (row < nq) Dt[row * K + col[j]] = d;
-                    m = fminf(m, d);
+            for (int g = 0; g < 4; ++g) {
+                const int cl = wc + j * 32 + 8 * g + 4 * h;     // local centroid of element 4g
+                const int64_t c = c0 + cl;
+                const float4 cv = *reinterpret_cast<const float4 *>(&cns[cl]);
+                float4 d;
+                d.x = fmaxf(fmaf(-2.f, acc[i][j][4 * g + 0], qr + cv.x), 0.f);
+                d.y = fmaxf(fmaf(-2.f, acc[i][j][4 * g + 1], qr + cv.y), 0.f);
+                d.z = fmaxf(fmaf(-2.f, acc[i][j][4 * g + 2], qr + cv.z), 0.f);
+                d.w = fmaxf(fmaf(-2.f, acc[i][j][4 * g + 3], qr + cv.w), 0.f);
+                if (c + 3 < K) {
+                    m = fminf(fminf(m, fminf(d.x, d.y)), fminf(d.z, d.w));
+                    if (q < nq) {
+                        if (vec) {
+                            *reinterpret_cast<float4 *>(rowp + c) = d;
+                        } else {
+                            rowp[c] = d.x; rowp[c + 1] = d.y; rowp[c + 2] = d.z; rowp[c + 3] = d.w;
+                        }
+                    }
+                } else {
+                    const float dv[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (c + e < K) {
+                            m = fminf(m, dv[e]);
+                            if (q < nq) rowp[c + e] = dv[e];
+                        }
                 }
-            // minimum over the 32 lanes that share the row: rotate-and-min inside each row of
-            // 16 (DPP row_ror 8/4/2/1), then lane 15 of rows 0/2 into rows 1/3 (row_bcast15)
-            m = fminf(m, dpp_float<0x128, 0xf>(m));
-            m = fminf(m, dpp_float<0x124, 0xf>(m));
-            m = fminf(m, dpp_float<0x122, 0xf>(m));
-            m = fminf(m, dpp_float<0x121, 0xf>(m));
-            m = fminf(m, dpp_float<0x142, 0xa>(m, INFINITY));
-            if (l32 == 16 && row < nq && blk < nb) bm[row * nb + blk] = m;
-        }
+            }
+        m = fminf(m, __shfl_xor(m, 32, WAVE));   // the other half holds the other 32 centroids
+        if (h == 0 && q < nq && blk < nb) bm[q * nb + blk] = m;
+    }
 }
 
 // Nearest centroid only (P = 1): the same tile product, reduced on the fly to
-// the per-row minimum of (distance, centroid id), merged across centroid tiles
-// with a 64-bit atomic minimum; no distance tile is written.  best[] must be
-// pre-filled with all ones.
+// the per-query minimum of (distance, centroid id), merged across centroid
+// tiles with a 64-bit atomic minimum; no distance tile is written.  best[]
+// must be pre-filled with all ones.
 __global__ __launch_bounds__(256) void coarse_argmin_kernel(
     const float *__restrict__ Q, const float *__restrict__ qn, int64_t nq,
     const float *__restrict__ C, const float *__restrict__ cn, int64_t K, int D,
@@ -151,41 +194,36 @@ __global__ __launch_bounds__(256) void coarse_argmin_kernel(
 {
     __shared__ __attribute__((aligned(16))) float As[GT * GLD];
     __shared__ __attribute__((aligned(16))) float Bs[GT * GLD];
+    __shared__ __attribute__((aligned(16))) float cns[GT];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t tile = blockIdx.x;
-    const int64_t q0 = (tile % tiles_q) * GT, c0 = (tile / tiles_q) * GT;
+    int64_t q0, c0;
+    if (!tile_of_block(blockIdx.x, tiles_q, q0, c0)) return;
     const int wq = (wave >> 1) * 64, wc = (wave & 1) * 64;
     const int l32 = lane & 31, h = lane >> 5;
+    if (threadIdx.x < GT) cns[threadIdx.x] = c0 + threadIdx.x < K ? cn[c0 + threadIdx.x] : 0.f;
     floatx16 acc[2][2];
     gemm_tile(Q, nq, q0, C, K, c0, D, As, Bs, acc);
-    float cnj[2];
-    int64_t col[2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        col[j] = c0 + wc + j * 32 + l32;
-        cnj[j] = col[j] < K ? cn[col[j]] : 0.f;
-    }
+    for (int i = 0; i < 2; ++i) {
+        const int64_t q = q0 + wq + i * 32 + l32;
+        const float qr = q < nq ? qn[q] : 0.f;
+        unsigned long long key = ~0ull;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            int64_t row = q0 + wq + i * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            float qr = row < nq ? qn[row] : 0.f;
-            unsigned long long key = ~0ull;
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                if (col[j] < K) {
-                    float d = fmaxf(fmaf(-2.f, acc[i][j][v], qr + cnj[j]), 0.f);
-                    unsigned long long kj = ((unsigned long long)float_key(d) << 32) | (uint32_t)col[j];
-                    key = kj < key ? kj : key;
+            for (int v = 0; v < 16; ++v) {
+                const int cl = wc + j * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                const int64_t c = c0 + cl;
+                if (c < K) {
+                    float d = fmaxf(fmaf(-2.f, acc[i][j][v], qr + cns[cl]), 0.f);
+                    unsigned long long kc = ((unsigned long long)float_key(d) << 32) | (uint32_t)c;
+                    key = kc < key ? kc : key;
                 }
-#pragma unroll
-            for (int o = 16; o > 0; o >>= 1) {   // stays inside the 32-lane half that shares the row
-                unsigned long long t = __shfl_xor(key, o, WAVE);
-                key = t < key ? t : key;
             }
-            if (l32 == 0 && row < nq) atomicMin(&best[row], key);
-        }
+        unsigned long long other = __shfl_xor(key, 32, WAVE);
+        key = other < key ? other : key;
+        if (h == 0 && q < nq) atomicMin(&best[q], key);
+    }
 }
 
 __global__ __launch_bounds__(256) void argmin_unpack_kernel(const unsigned long long *__restrict__ best,

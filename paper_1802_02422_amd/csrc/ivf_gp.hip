@@ -100,7 +100,7 @@ int launch_coarse(const float *x, const float *xn, int64_t nq, const float *C, c
     const int nb = (int)((K + BMW - 1) / BMW);
     int tiles_q = (int)((nq + GT - 1) / GT);
     int64_t tiles_c = (K + GT - 1) / GT;
-    int64_t grid = tiles_q * tiles_c;
+    int64_t grid = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * tiles_c;
     if (grid >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
     coarse_gemm_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(x, xn, nq, C, cn, K, D, Dt, bm, nb, tiles_q);
     LAUNCHCHK("coarse_gemm_kernel");
@@ -447,7 +447,7 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
                 row_norm_kernel<<<dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st>>>(x + q0 * D, n, D, xn);
                 LAUNCHCHK("row_norm_kernel");
                 int tiles_q = (int)((n + GT - 1) / GT);
-                int64_t grid = tiles_q * ((K + GT - 1) / GT);
+                int64_t grid = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * ((K + GT - 1) / GT);
                 if (grid >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
                 coarse_argmin_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(x + q0 * D, xn, n, centroids, cn, K, D, best, tiles_q);
                 LAUNCHCHK("coarse_argmin_kernel");
