@@ -59,3 +59,13 @@ def tiny():
 @pytest.fixture
 def rng():
     return np.random.default_rng(20180207)
+
+
+@pytest.fixture(scope="session")
+def small():
+    return make_workload("small")
+
+
+@pytest.fixture(scope="session")
+def small_sift():
+    return make_workload("small_sift")

@@ -1,0 +1,89 @@
+"""Parity at sizes that span many kernel tiles with ragged tails, on the SIFT-like data,
+and at the full benchmark sizes on sampled queries (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import synthdata as sd
+import paper_1802_02422_amd as ivf
+from paper_1802_02422_amd import index_builder
+from oracle import ivf_oracle as orc
+import parity
+from bench import download_index
+
+
+def run_and_check(ix, Q, spec, sample=None, nprobe=None, tau=None, k=None, max_near_frac=0.05):
+    nprobe, tau, k = nprobe or spec.nprobe, tau or spec.prune_frac, k or spec.k
+    handle = ivf.ivf_load_index(parity.to_device(ix))
+    out = parity.run_gpu_search(handle, Q, nprobe, tau, k)
+    ivf.ivf_free_index(handle)
+    if sample is not None:
+        out = {n: v[sample] for n, v in out.items()}
+        Q = Q[sample]
+    rep = parity.check_search(ix, Q, nprobe, tau, k, out)
+    print(rep, flush=True)
+    rep.assert_ok(max_near_frac=max_near_frac)
+    return rep
+
+
+def test_small_deep_many_tiles(small):
+    spec, ix, Q, X = small          # K = 2000 (not a multiple of 128), nq = 333, M = 16, L = 24
+    print("case: small", spec, flush=True)
+    run_and_check(ix, Q, spec)
+    run_and_check(ix, Q[:130], spec, nprobe=7, tau=1.0, k=1)
+    run_and_check(ix, Q[:9], spec, nprobe=300, tau=0.05, k=300)
+
+
+def test_small_sift_like(small_sift):
+    spec, ix, Q, X = small_sift     # D = 128, uint8-valued components, K = 1000
+    print("case: small_sift", spec, flush=True)
+    run_and_check(ix, Q, spec)
+
+
+def test_k_not_multiple_of_four_and_tiny_lists():
+    """K = 509: scalar store path of the distance tile, partial last block of 64, L close to K."""
+    mix = sd.make_mixture("deep", 100, 32)
+    X = sd.draw_points(mix, 6000, 0, "odd-base")[0].numpy()
+    Xt = sd.draw_points(mix, 4000, 0, "odd-train")[0].numpy()
+    Q = sd.draw_queries(mix, 70, "odd-query").numpy()
+    ix = orc.build_index(Xt, X, 509, 5, 8, sd.draw_indices(4000, 509, "odd-k").numpy(),
+                         sd.draw_indices(4000, 256, "odd-pq").numpy(), kmeans_iters=3, pq_iters=3)
+    spec = sd.WorkloadSpec("odd", "deep", 6000, 32, 100, 509, 5, 8, 70, 33, 0.4, 20, 4000)
+    print("case: odd K", flush=True)
+    run_and_check(ix, Q, spec, max_near_frac=0.1)
+    run_and_check(ix, Q, spec, nprobe=509, tau=1.0, k=64, max_near_frac=0.1)     # exhaustive
+
+
+def full_size_case(name, n_sample):
+    spec = sd.WORKLOADS[name]
+    dev = torch.device("cuda:0")
+    mix = sd.make_mixture(spec.kind, spec.n_mix, spec.D, dev)
+    mode = "mixture" if spec.K >= (1 << 18) else "kmeans"
+    desc, stats = index_builder.build(spec, mix, mode=mode)
+    print("built", name, stats, flush=True)
+    Q = sd.draw_queries(mix, spec.nq).contiguous()
+    ix = download_index(desc, spec)
+    handle = ivf.ivf_load_index(desc)
+    desc.codes = desc.const_byte = desc.ids = None
+    torch.cuda.empty_cache()
+    ivf.ivf_set_scratch_limit(handle, 48 << 30)              # the launch configuration bench.py times
+    out = ivf.ivf_search_stages(handle, Q, spec.nprobe, spec.prune_frac, spec.k)
+    torch.cuda.synchronize()
+    sample = np.linspace(0, spec.nq - 1, n_sample).astype(np.int64)
+    out = {n: v[torch.from_numpy(sample).to(dev)].cpu().numpy() for n, v in out.items()}
+    ivf.ivf_free_index(handle)
+    rep = parity.check_search(ix, Q.cpu().numpy()[sample], spec.nprobe, spec.prune_frac, spec.k, out)
+    print(name, rep, flush=True)
+    rep.assert_ok(max_near_frac=0.1)
+
+
+def test_full_size_deep10m_sampled_queries():
+    print("case: deep10m full size", flush=True)
+    full_size_case("deep10m", 64)
+
+
+def test_full_size_deep1b_sampled_queries():
+    print("case: deep1b full size", flush=True)
+    full_size_case("deep1b", 32)
