@@ -21,6 +21,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 DESC_BYTES = 16          # one kept-subregion descriptor read by the scan
 
+# HBM bytes per scan launch from rocprofv3 hardware counters (FETCH_SIZE and WRITE_SIZE, each scaled by what
+# the same counter reads for the library's plain 1 GiB copy kernel: 2.0 and 1.0).  Measured offline with the
+# commands in profiles/scan_kernel_<workload>.md; None where no counter run has been made.
+MEASURED_SCAN_TRAFFIC_BYTES = {"deep1b": (5_181_100 * 2.0 + 31_648 * 1.0) * 1024}
+
 
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
@@ -159,7 +164,8 @@ def main():
         "stage_ms_per_step": {k_: v / args.steps for k_, v in stage_ms.items()},
         "coarse_gemm_tflops": coarse_tflops,
         "roofline": {"kernel": "scan_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_SCAN_TRAFFIC_BYTES.get(spec.name),
                      "launches": scan_launches, "avg_launch_ms": scan_ms, "algorithmic_bytes_per_launch": algo_bytes},
     }
     if copy_gbs is not None:
