@@ -106,7 +106,7 @@ int ivf_set_scratch_limit(ivf_index *index, int64_t bytes);
  * out_ids [nq][k] int32 and out_dists [nq][k] fp32 (estimated squared L2
  * distance); rows with fewer than k candidates are padded with id -1 and
  * +inf.  1 <= nprobe <= min(K, 4096), 0 < prune_frac <= 1,
- * 1 <= k <= IVF_MAX_K_RESULTS, nprobe*L <= 2^20.  All arithmetic is fp32.
+ * 1 <= k <= IVF_MAX_K_RESULTS, nprobe*L <= 32000.  All arithmetic is fp32.
  * Asynchronous on hip_stream; the handle's scratch is reused by every call,
  * so calls on one handle must not overlap.
  */
@@ -176,8 +176,8 @@ int ivf_alpha_stats(const float *centroids, int64_t K, int D, const int32_t *nbr
  * Per-stage device timing of ivf_search / ivf_search_stages on a handle.  While
  * enabled, every pass over a tile of queries records HIP events on the caller's
  * stream around its seven kernel groups, in launch order:
- *   0 query norms + coarse distance GEMM   1 nprobe selection   2 Eq. (7) scoring
- *   3 pruning select   4 lookup tables   5 ADC scan   6 final k-select
+ *   0 query norms + coarse distance GEMM   1 nprobe selection   2 Eq. (7) scoring fused with
+ *   the pruning select   3 (empty)   4 lookup tables   5 ADC scan   6 final k-select
  * ivf_profile_read waits for the device, writes the summed milliseconds per
  * group to stage_ms[IVF_N_STAGES] (host) and the number of passes to *launches
  * (host), and resets the counters.

@@ -131,7 +131,7 @@ struct ivf_index {
     uint32_t *sub_offsets = nullptr, *blk_off = nullptr;
     uint8_t *blocks = nullptr;
     int64_t scratch_limit = 8ll << 30;
-    Buf dt, bm, qn, probe_id, probe_d, scores, desc, lut, partial;
+    Buf dt, bm, qn, probe_id, probe_d, desc, lut, partial;
     // optional per-stage timing with HIP events on the caller's stream
     bool profile = false;
     std::vector<hipEvent_t> ev[IVF_N_STAGES + 1];   // ev[s][i], ev[s+1][i] bracket stage s of pass i
@@ -155,7 +155,7 @@ extern "C" void ivf_free_index(ivf_index *ix)
     (void)hipDeviceSynchronize();
     void *owned[] = {ix->centroids, ix->cnorm, ix->alpha, ix->cst, ix->codebook, ix->const_table,
                      ix->nbr, ix->ids, ix->sub_offsets, ix->blk_off, ix->blocks, ix->dt.p, ix->bm.p, ix->qn.p,
-                     ix->probe_id.p, ix->probe_d.p, ix->scores.p, ix->desc.p, ix->lut.p, ix->partial.p};
+                     ix->probe_id.p, ix->probe_d.p, ix->desc.p, ix->lut.p, ix->partial.p};
     for (void *p : owned)
         if (p) (void)hipFree(p);
     delete ix;
@@ -271,7 +271,7 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
     const int P = nprobe, L = ix->L, M = ix->M, D = ix->D;
     const int64_t K = ix->K;
     const int64_t PL = (int64_t)P * L;
-    if (PL > (1 << 20)) return fail(IVF_EINVAL, "nprobe*L=%lld exceeds 2^20", (long long)PL);
+    if (PL > 32000) return fail(IVF_EINVAL, "nprobe*L=%lld exceeds 32000", (long long)PL);
     const int S = (int)ivf_num_kept(P, L, prune_frac);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
@@ -297,13 +297,19 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
     if ((rc = ensure(ix->qn, (size_t)tile * sizeof(float)))) return rc;
     if ((rc = ensure(ix->probe_id, (size_t)tile * P * sizeof(int32_t)))) return rc;
     if ((rc = ensure(ix->probe_d, (size_t)tile * P * sizeof(float)))) return rc;
-    if ((rc = ensure(ix->scores, (size_t)tile * PL * sizeof(float)))) return rc;
     if ((rc = ensure(ix->desc, (size_t)tile * S * sizeof(SubDesc)))) return rc;
     if ((rc = ensure(ix->lut, (size_t)tile * M * 256 * sizeof(float)))) return rc;
     if ((rc = ensure(ix->partial, (size_t)tile * merge_n * sizeof(uint64_t)))) return rc;
 
     const size_t scan_lds = (size_t)SCAN_WAVES * pool_capacity(k) * sizeof(uint64_t);   // dynamic part: the pools
     const size_t merge_lds = (size_t)merge_pow2 * sizeof(uint64_t);
+    const size_t sp_lds = (size_t)(PL + 3 * P) * sizeof(uint32_t);
+    if (sp_lds > 128 * 1024) return fail(IVF_EINVAL, "nprobe*L=%lld exceeds the 32768 scores one workgroup holds", (long long)PL);
+    if (sp_lds > 48 * 1024) {
+        const void *fn = PL > 4096 ? reinterpret_cast<const void *>(&score_prune_kernel<1024>)
+                                   : reinterpret_cast<const void *>(&score_prune_kernel<256>);
+        HIPCHK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sp_lds));
+    }
     if (scan_lds > 32 * 1024) {   // dynamic + static LDS above the default 64 KB window
         const void *fn = M == 16 ? reinterpret_cast<const void *>(&scan_kernel<16>)
                                  : reinterpret_cast<const void *>(&scan_kernel<8>);
@@ -318,7 +324,6 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
         float *bm = static_cast<float *>(ix->bm.p);
         int32_t *pid = probe_id_out ? probe_id_out + q0 * P : static_cast<int32_t *>(ix->probe_id.p);
         float *pd = probe_d_out ? probe_d_out + q0 * P : static_cast<float *>(ix->probe_d.p);
-        float *scores = static_cast<float *>(ix->scores.p);
         SubDesc *desc = static_cast<SubDesc *>(ix->desc.p);
         float *lut = static_cast<float *>(ix->lut.p);
         uint64_t *partial = static_cast<uint64_t *>(ix->partial.p);
@@ -339,21 +344,16 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
         if ((rc = launch_probe_select(Dt, bm, n, K, P, pid, pd, st))) return rc;
         if ((rc = mark(2))) return rc;
 
-        const int64_t total = n * PL;
-        score_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
-            Dt, K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, scores, total);
-        LAUNCHCHK("score_kernel");
-        if ((rc = mark(3))) return rc;
-
         int64_t *ks = kept_sub_out ? kept_sub_out + q0 * S : nullptr;
         int64_t *ns = n_scanned_out ? n_scanned_out + q0 : nullptr;
-        if (PL > 8192)
-            prune_kernel<1024><<<dim3((unsigned)n), dim3(1024), 0, st>>>(
-                scores, (int)PL, S, pid, P, L, ix->sub_offsets, ix->blk_off, desc, ks, ns);
+        if (PL > 4096)
+            score_prune_kernel<1024><<<dim3((unsigned)n), dim3(1024), sp_lds, st>>>(
+                Dt, K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_offsets, ix->blk_off, desc, ks, ns);
         else
-            prune_kernel<256><<<dim3((unsigned)n), dim3(256), 0, st>>>(
-                scores, (int)PL, S, pid, P, L, ix->sub_offsets, ix->blk_off, desc, ks, ns);
-        LAUNCHCHK("prune_kernel");
+            score_prune_kernel<256><<<dim3((unsigned)n), dim3(256), sp_lds, st>>>(
+                Dt, K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_offsets, ix->blk_off, desc, ks, ns);
+        LAUNCHCHK("score_prune_kernel");
+        if ((rc = mark(3))) return rc;
         if ((rc = mark(4))) return rc;
 
         lut_kernel<<<dim3((unsigned)n), dim3(256), (size_t)D * sizeof(float), st>>>(Q, D, M, ix->codebook, lut);

@@ -14,50 +14,57 @@ struct SubDesc {
     float base;      // distance from the query to the subcentroid
 };
 
-// score[q][p][l] = (1-a) D[q][r] + a D[q][nbr[r][l]] + cst[r][l], r = probe_id[q][p],
-// cst[r][l] = -a(1-a)||c_r - s_l||^2 tabulated at load time.  The neighbour
-// distances are gathered from the stage-1 distance tile, not recomputed.
-__global__ __launch_bounds__(256) void score_kernel(
+// Stages 2 and 3 fused, one workgroup per query.
+// Stage 2 (Eq. (7)): score[p][l] = (1-a) D[q][r] + a D[q][nbr[r][l]] + cst[r][l], r = probe_id[q][p],
+// cst[r][l] = -a(1-a)||c_r - s_l||^2 tabulated at load time.  The neighbour distances are gathered from
+// the stage-1 distance tile, not recomputed; every thread has PL/BLOCK independent gathers in flight.
+// The scores never leave the chip: they are kept in LDS as order-preserving keys.
+// Stage 3: keep the S smallest of the P*L scores by (score, r*L + l).  probe_id is ascending in r, so
+// position order in the score row is subregion-id order and the descriptors come out sorted by address.
+// Dynamic LDS: P*L keys + P probe ids + P probe distances + P alphas.
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void score_prune_kernel(
     const float *__restrict__ Dt, int64_t K, const int32_t *__restrict__ probe_id,
     const float *__restrict__ probe_d, int P, int L, const int32_t *__restrict__ nbr,
-    const float *__restrict__ cst, const float *__restrict__ alpha, float *__restrict__ scores,
-    int64_t total)
-{
-    int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    int l = (int)(idx % L);
-    int64_t qp = idx / L;
-    int64_t q = qp / P;
-    int64_t r = probe_id[qp];
-    float a = alpha[r];
-    float dr = probe_d[qp];
-    float ds = Dt[q * K + nbr[r * L + l]];
-    scores[idx] = fmaf(a, ds, fmaf(1.f - a, dr, cst[r * L + l]));
-}
-
-// Keep the S smallest of the P*L scores of each query by (score, r*L + l).
-// probe_id is ascending in r, so position order in the score row is
-// subregion-id order and the descriptors come out sorted by address.
-template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void prune_kernel(
-    const float *__restrict__ scores, int PL, int S, const int32_t *__restrict__ probe_id, int P,
-    int L, const uint32_t *__restrict__ sub_offsets, const uint32_t *__restrict__ blk_off,
+    const float *__restrict__ cst, const float *__restrict__ alpha, int S,
+    const uint32_t *__restrict__ sub_offsets, const uint32_t *__restrict__ blk_off,
     SubDesc *__restrict__ desc, int64_t *__restrict__ kept_sub, int64_t *__restrict__ n_scanned)
 {
     __shared__ SelectShared sh;
     __shared__ unsigned long long codes_total;
+    extern __shared__ __attribute__((aligned(16))) uint32_t dyn[];
+    const int PL = P * L;
+    uint32_t *keys = dyn;
+    int32_t *pid = reinterpret_cast<int32_t *>(dyn + PL);
+    float *pd = reinterpret_cast<float *>(dyn + PL + P);
+    float *pa = reinterpret_cast<float *>(dyn + PL + 2 * P);
     const int64_t q = blockIdx.x;
-    const float *row = scores + q * PL;
+    const float *row = Dt + q * K;
+    for (int p = threadIdx.x; p < P; p += BLOCK) {
+        const int32_t r = probe_id[q * P + p];
+        pid[p] = r;
+        pd[p] = probe_d[q * P + p];
+        pa[p] = alpha[r];
+    }
     if (threadIdx.x == 0) codes_total = 0;
-    auto key = [row](int64_t i) { return float_key(row[i]); };
+    __syncthreads();
+#pragma unroll 4
+    for (int i = threadIdx.x; i < PL; i += BLOCK) {
+        const int p = i / L, l = i - p * L;
+        const int64_t r = pid[p];
+        const float a = pa[p];
+        const float ds = row[nbr[r * L + l]];
+        keys[i] = float_key(fmaf(a, ds, fmaf(1.f - a, pd[p], cst[r * L + l])));
+    }
+    __syncthreads();
+    auto key = [keys](int64_t i) { return keys[i]; };
     uint32_t pivot, need;
     block_radix_select<BLOCK>(key, PL, (uint32_t)S, sh, pivot, need);
     unsigned long long mine = 0;
     block_emit_selected<BLOCK>(key, PL, (uint32_t)S, pivot, need, sh,
                                [&](uint32_t pos, int64_t i, uint32_t k) {
-                                   int64_t r = probe_id[q * P + i / L];
-                                   int64_t b = r * L + (i % L);
-                                   uint32_t p0 = sub_offsets[b], p1 = sub_offsets[b + 1];
+                                   const int64_t b = (int64_t)pid[i / L] * L + (i % L);
+                                   const uint32_t p0 = sub_offsets[b], p1 = sub_offsets[b + 1];
                                    SubDesc d;
                                    d.blk = blk_off[b];
                                    d.pos0 = p0;
