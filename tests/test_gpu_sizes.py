@@ -56,7 +56,7 @@ def test_k_not_multiple_of_four_and_tiny_lists():
     run_and_check(ix, Q, spec, nprobe=509, tau=1.0, k=64, max_near_frac=0.1)     # exhaustive
 
 
-def full_size_case(name, n_sample):
+def full_size_case(name, n_sample, extra_batches=()):
     spec = sd.WORKLOADS[name]
     dev = torch.device("cuda:0")
     mix = sd.make_mixture(spec.kind, spec.n_mix, spec.D, dev)
@@ -73,15 +73,32 @@ def full_size_case(name, n_sample):
     torch.cuda.synchronize()
     sample = np.linspace(0, spec.nq - 1, n_sample).astype(np.int64)
     out = {n: v[torch.from_numpy(sample).to(dev)].cpu().numpy() for n, v in out.items()}
-    ivf.ivf_free_index(handle)
     rep = parity.check_search(ix, Q.cpu().numpy()[sample], spec.nprobe, spec.prune_frac, spec.k, out)
     print(name, rep, flush=True)
     rep.assert_ok(max_near_frac=0.1)
+    for nb in extra_batches:                                 # other batch sizes of the same workload
+        o2 = ivf.ivf_search_stages(handle, Q[:nb].contiguous(), spec.nprobe, spec.prune_frac, spec.k)
+        torch.cuda.synchronize()
+        o2 = {n: v.cpu().numpy() for n, v in o2.items()}
+        rep = parity.check_search(ix, Q[:nb].cpu().numpy(), spec.nprobe, spec.prune_frac, spec.k, o2)
+        print(name, "batch", nb, rep, flush=True)
+        rep.assert_ok(max_near_frac=0.1)
+    ivf.ivf_free_index(handle)
 
 
 def test_full_size_deep10m_sampled_queries():
     print("case: deep10m full size", flush=True)
     full_size_case("deep10m", 64)
+
+
+def test_full_size_sift10m_sampled_queries():
+    print("case: sift10m full size", flush=True)
+    full_size_case("sift10m", 64)
+
+
+def test_full_size_deep100m_latency_batches():
+    print("case: deep100m full size, nq = 64 and nq = 1", flush=True)
+    full_size_case("deep100m", 64, extra_batches=(1,))
 
 
 def test_full_size_deep1b_sampled_queries():
