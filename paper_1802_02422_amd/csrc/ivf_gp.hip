@@ -158,6 +158,8 @@ extern "C" void ivf_free_index(ivf_index *ix)
                      ix->probe_id.p, ix->probe_d.p, ix->desc.p, ix->lut.p, ix->partial.p};
     for (void *p : owned)
         if (p) (void)hipFree(p);
+    for (auto &v : ix->ev)
+        for (hipEvent_t e : v) (void)hipEventDestroy(e);
     delete ix;
 }
 
