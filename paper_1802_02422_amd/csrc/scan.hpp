@@ -159,8 +159,7 @@ struct ChunkRegs {
     typename CodeWord<M>::type code[SCAN_U];
     uint32_t cb[SCAN_U];        // constant byte
     float base[SCAN_U];
-    uint32_t own[SCAN_U];       // owning descriptor (lane of the batch), 0xFFFFFFFF = no record
-    uint32_t c[SCAN_U];         // record index inside its subregion
+    uint32_t c[SCAN_U];         // grouped position of the record (indexes ids[]); 0xFFFFFFFF = no record
 };
 
 // Find the owner of every record of the chunk starting at flattened index t0
@@ -193,8 +192,7 @@ __device__ __forceinline__ void scan_issue(ChunkRegs<M> &r, WaveStage &st, uint3
         const uint4 db = st.b[oi];
         const uint32_t c = t - db.x;
         act = act && c < db.y;                     // never read outside the owner's block
-        r.own[u] = act ? oi : 0xFFFFFFFFu;
-        r.c[u] = c;
+        r.c[u] = act ? db.w + c : 0xFFFFFFFFu;
         r.base[u] = __uint_as_float(db.z);
         r.cb[u] = 0;
         if (act) {
@@ -225,7 +223,7 @@ __device__ __forceinline__ void scan_issue(ChunkRegs<M> &r, WaveStage &st, uint3
 // Output: per (q, split, wave) the k best keys (distance, position), in no
 // particular order, padded with EMPTY_KEY.
 template <int M>
-__global__ __launch_bounds__(SCAN_BLOCK) void scan_kernel(
+__global__ __launch_bounds__(SCAN_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4))) void scan_kernel(
     const uint8_t *__restrict__ blocks, const float *__restrict__ const_table,
     const SubDesc *__restrict__ desc, int S, const float *__restrict__ lut, int k, int nsplit,
     uint64_t *__restrict__ partial)
@@ -265,64 +263,68 @@ __global__ __launch_bounds__(SCAN_BLOCK) void scan_kernel(
     int pool_n = 0;
     float theta = INFINITY;
 
+    // The wavefront's descriptors form one stream of chunks that runs across batch boundaries:
+    // next() stages the next batch when the current one is exhausted (the stage is only read
+    // while issuing) and issues the following chunk into the given register set.
     SubDesc sd_next;
     sd_next.blk = 0; sd_next.pos0 = 0; sd_next.len = 0; sd_next.base = 0.f;
-    {
-        const int d = d_begin + wave * WAVE + lane;
-        if (d < d_end) sd_next = qd[d];
-    }
-    for (int b0 = d_begin + wave * WAVE; b0 < d_end; b0 += SCAN_WAVES * WAVE) {
-        const SubDesc sd = sd_next;
-        {   // prefetch the next batch's descriptors
-            const int d = b0 + SCAN_WAVES * WAVE + lane;
+    int b_next = d_begin + wave * WAVE;          // first descriptor of the batch to stage next
+    if (b_next + lane < d_end) sd_next = qd[b_next + lane];
+    uint32_t len = 0, pre = 0, Tn = 0, t_next = 0, carry = 0;
+    auto next = [&](ChunkRegs<M> &r) -> bool {
+        while (t_next >= Tn) {                    // current batch exhausted (or empty): stage the next one
+            if (b_next >= d_end) return false;
+            const SubDesc sd = sd_next;
+            b_next += SCAN_WAVES * WAVE;
             sd_next.blk = 0; sd_next.pos0 = 0; sd_next.len = 0; sd_next.base = 0.f;
-            if (d < d_end) sd_next = qd[d];
-        }
-        const uint32_t len = sd.len;
-        const uint32_t inc = wave_inclusive_scan(len);
-        const uint32_t pre = inc - len;
-        const uint32_t Tn = (uint32_t)__builtin_amdgcn_readlane((int)inc, WAVE - 1);
-        wave_sync();
-        {
+            if (b_next + lane < d_end) sd_next = qd[b_next + lane];   // prefetch the batch after
+            len = sd.len;
+            const uint32_t inc = wave_inclusive_scan(len);
+            pre = inc - len;
+            Tn = (uint32_t)__builtin_amdgcn_readlane((int)inc, WAVE - 1);
+            t_next = 0;
+            carry = 0;
+            wave_sync();
             const uint64_t pc = reinterpret_cast<uint64_t>(blocks) + (uint64_t)sd.blk * 64u;
             const uint64_t pb = pc + (uint64_t)len * M;
             st.a[lane] = make_uint4((uint32_t)pc, (uint32_t)(pc >> 32), (uint32_t)pb, (uint32_t)(pb >> 32));
             st.b[lane] = make_uint4(pre, len, __float_as_uint(sd.base), sd.pos0);
         }
-        uint32_t carry = 0;
-        // two register sets used alternately: the loads of chunk c+1 are in flight while chunk c is consumed
-        ChunkRegs<M> ra, rb;
-        auto consume = [&](ChunkRegs<M> &cur) {
-            theta = fminf(theta, key_float(wg_theta_key));
+        scan_issue<M>(r, st, t_next, Tn, len, pre, carry);
+        t_next += SCAN_CHUNK;
+        return true;
+    };
+    auto consume = [&](ChunkRegs<M> &cur) {
+        theta = fminf(theta, key_float(wg_theta_key));
 #pragma unroll
-            for (int u = 0; u < SCAN_U; ++u) {
-                const bool active = cur.own[u] != 0xFFFFFFFFu;
-                float dist = INFINITY;
-                if (active) dist = adc_sum<M>(cur.code[u], Tb, cur.base[u] + nt[cur.cb[u]], two);
-                const bool pass = active && dist <= theta;
-                const uint64_t mask = __ballot(pass);
-                if (mask) {
-                    if (pass) {
-                        int slot = pool_n + __popcll(mask & ((1ull << lane) - 1ull));
-                        pool[slot] = ((uint64_t)float_key(dist) << 32) | (st.b[cur.own[u]].w + cur.c[u]);
-                    }
-                    pool_n += __popcll(mask);
-                    if (pool_n > cap - WAVE) {
-                        theta = wave_pool_compact(pool, cap, pool_n, k);
-                        if (lane == 0) atomicMin(&wg_theta_key, float_key(theta));
-                    }
+        for (int u = 0; u < SCAN_U; ++u) {
+            const bool active = cur.c[u] != 0xFFFFFFFFu;
+            float dist = INFINITY;
+            if (active) dist = adc_sum<M>(cur.code[u], Tb, cur.base[u] + nt[cur.cb[u]], two);
+            const bool pass = active && dist <= theta;
+            const uint64_t mask = __ballot(pass);
+            if (mask) {
+                if (pass) {
+                    int slot = pool_n + __popcll(mask & ((1ull << lane) - 1ull));
+                    pool[slot] = ((uint64_t)float_key(dist) << 32) | cur.c[u];
+                }
+                pool_n += __popcll(mask);
+                if (pool_n > cap - WAVE) {
+                    theta = wave_pool_compact(pool, cap, pool_n, k);
+                    if (lane == 0) atomicMin(&wg_theta_key, float_key(theta));
                 }
             }
-        };
-        if (Tn > 0) scan_issue<M>(ra, st, 0u, Tn, len, pre, carry);
-        for (uint32_t t0 = 0; t0 < Tn; t0 += 2 * SCAN_CHUNK) {
-            const bool more1 = t0 + SCAN_CHUNK < Tn;
-            if (more1) scan_issue<M>(rb, st, t0 + SCAN_CHUNK, Tn, len, pre, carry);
-            consume(ra);
-            if (!more1) break;
-            if (t0 + 2 * SCAN_CHUNK < Tn) scan_issue<M>(ra, st, t0 + 2 * SCAN_CHUNK, Tn, len, pre, carry);
-            consume(rb);
         }
+    };
+    // two register sets used alternately: the loads of chunk c+1 are in flight while chunk c is consumed
+    ChunkRegs<M> ra, rb;
+    bool va = next(ra);
+    while (va) {
+        const bool vb = next(rb);
+        consume(ra);
+        if (!vb) break;
+        va = next(ra);
+        consume(rb);
     }
     wave_pool_compact(pool, cap, pool_n, k);
     uint64_t *out = partial + ((q * nsplit + split) * SCAN_WAVES + wave) * (int64_t)k;

@@ -25,7 +25,17 @@ __device__ void block_radix_select(KeyFn key, int64_t n, uint32_t nsel, SelectSh
     for (int shift = 24; shift >= 0; shift -= 8) {
         for (int i = tid; i < 256; i += BLOCK) sh.hist[i] = 0;
         __syncthreads();
-        for (int64_t i = tid; i < n; i += BLOCK) {
+        // several independent key reads in flight per thread before their histogram updates
+        int64_t i = tid;
+        for (; i + 3 * BLOCK < n; i += 4 * BLOCK) {
+            uint32_t k[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) k[u] = key(i + u * BLOCK);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if ((k[u] & mask) == prefix) atomicAdd(&sh.hist[(k[u] >> shift) & 255u], 1u);
+        }
+        for (; i < n; i += BLOCK) {
             uint32_t k = key(i);
             if ((k & mask) == prefix) atomicAdd(&sh.hist[(k >> shift) & 255u], 1u);
         }

@@ -56,6 +56,28 @@ def test_k_not_multiple_of_four_and_tiny_lists():
     run_and_check(ix, Q, spec, nprobe=509, tau=1.0, k=64, max_near_frac=0.1)     # exhaustive
 
 
+def test_long_lists_duplicates_and_empty_regions():
+    """Few regions (lists of thousands of records, many chunks per descriptor), exact duplicate
+    points (exact distance ties) and regions that stay empty."""
+    mix = sd.make_mixture("deep", 6, 32, name="degenerate")
+    X = sd.draw_points(mix, 30000, 0, "deg-base")[0].numpy()
+    X[5000:7000] = X[4999]                      # 2001 identical points
+    X[20000:20300] = X[123]
+    Xt = sd.draw_points(mix, 5000, 0, "deg-train")[0].numpy()
+    Q = sd.draw_queries(mix, 40, "deg-query").numpy()
+    Q[0] = X[4999]
+    Q[1] = X[123]
+    ix = orc.build_index(Xt, X, 12, 3, 16, sd.draw_indices(5000, 12, "deg-k").numpy(),
+                         sd.draw_indices(5000, 256, "deg-pq").numpy(), kmeans_iters=3, pq_iters=3)
+    sizes = np.diff(ix.sub_offsets.astype(np.int64))
+    print("case: degenerate; list sizes", sizes.tolist(), flush=True)
+    assert sizes.max() > 2000
+    spec = sd.WorkloadSpec("deg", "deep", 30000, 32, 6, 12, 3, 16, 40, 5, 0.5, 50, 5000)
+    run_and_check(ix, Q, spec, max_near_frac=1.0)
+    run_and_check(ix, Q, spec, nprobe=12, tau=1.0, k=1024, max_near_frac=1.0)
+    run_and_check(ix, Q[:3], spec, nprobe=1, tau=0.3, k=7, max_near_frac=1.0)
+
+
 def full_size_case(name, n_sample, extra_batches=()):
     spec = sd.WORKLOADS[name]
     dev = torch.device("cuda:0")
