@@ -123,14 +123,17 @@ __device__ __forceinline__ bool tile_of_block(int64_t b, int tiles_q, int64_t &q
 // Dt[q][j] = max(0, qn[q] + cn[j] - 2 <Q[q], C[j]>), and bm[q][b] = the minimum
 // of Dt[q][64b .. 64b+63] (each wavefront's 64-centroid quadrant gives one block
 // minimum per query).  The grid has 8 * ceil(tiles_q / 8) * tiles_c workgroups.
+constexpr int SLD = 64 + 4;   // row stride (floats) of a wavefront's 32x64 output staging area in LDS
+
 __global__ __launch_bounds__(256) void coarse_gemm_kernel(
     const float *__restrict__ Q, const float *__restrict__ qn, int64_t nq,
     const float *__restrict__ C, const float *__restrict__ cn, int64_t K, int D,
     float *__restrict__ Dt, float *__restrict__ bm, int nb, int tiles_q)
 {
-    __shared__ __attribute__((aligned(16))) float As[GT * GLD];
-    __shared__ __attribute__((aligned(16))) float Bs[GT * GLD];
+    __shared__ __attribute__((aligned(16))) float ops[2 * GT * GLD];   // operands; reused as output staging
     __shared__ __attribute__((aligned(16))) float cns[GT];
+    static_assert(4 * 32 * SLD <= 2 * GT * GLD, "the four staging areas must fit the operand buffers");
+    float *As = ops, *Bs = ops + GT * GLD;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     int64_t q0, c0;
     if (!tile_of_block(blockIdx.x, tiles_q, q0, c0)) return;
@@ -138,48 +141,57 @@ __global__ __launch_bounds__(256) void coarse_gemm_kernel(
     const int l32 = lane & 31, h = lane >> 5;
     if (threadIdx.x < GT) cns[threadIdx.x] = c0 + threadIdx.x < K ? cn[c0 + threadIdx.x] : 0.f;
     floatx16 acc[2][2];
-    gemm_tile(Q, nq, q0, C, K, c0, D, As, Bs, acc);   // ends with a barrier: cns is visible
+    gemm_tile(Q, nq, q0, C, K, c0, D, As, Bs, acc);   // ends with a barrier: cns is visible, operands are dead
     const bool vec = (K & 3) == 0;
     const int64_t blk = (c0 + wc) / BMW;
+    float *stage = ops + wave * (32 * SLD);
+    const int sr = lane >> 4, sc = (lane & 15) * 4;   // store phase: 16 lanes cover one query row of 64 centroids
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int64_t q = q0 + wq + i * 32 + l32;
         const float qr = q < nq ? qn[q] : 0.f;
-        float *rowp = Dt + q * K;
         float m = INFINITY;
+        // distances of 32 queries x 64 centroids into the staging area, [query][centroid]
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int cl = wc + j * 32 + 8 * g + 4 * h;     // local centroid of element 4g
-                const int64_t c = c0 + cl;
-                const float4 cv = *reinterpret_cast<const float4 *>(&cns[cl]);
+                const int cl = j * 32 + 8 * g + 4 * h;          // centroid of element 4g inside the quadrant
+                const int64_t c = c0 + wc + cl;
+                const float4 cv = *reinterpret_cast<const float4 *>(&cns[wc + cl]);
                 float4 d;
                 d.x = fmaxf(fmaf(-2.f, acc[i][j][4 * g + 0], qr + cv.x), 0.f);
                 d.y = fmaxf(fmaf(-2.f, acc[i][j][4 * g + 1], qr + cv.y), 0.f);
                 d.z = fmaxf(fmaf(-2.f, acc[i][j][4 * g + 2], qr + cv.z), 0.f);
                 d.w = fmaxf(fmaf(-2.f, acc[i][j][4 * g + 3], qr + cv.w), 0.f);
-                if (c + 3 < K) {
-                    m = fminf(fminf(m, fminf(d.x, d.y)), fminf(d.z, d.w));
-                    if (q < nq) {
-                        if (vec) {
-                            *reinterpret_cast<float4 *>(rowp + c) = d;
-                        } else {
-                            rowp[c] = d.x; rowp[c + 1] = d.y; rowp[c + 2] = d.z; rowp[c + 3] = d.w;
-                        }
-                    }
+                m = fminf(m, c + 0 < K ? d.x : INFINITY);
+                m = fminf(m, c + 1 < K ? d.y : INFINITY);
+                m = fminf(m, c + 2 < K ? d.z : INFINITY);
+                m = fminf(m, c + 3 < K ? d.w : INFINITY);
+                *reinterpret_cast<float4 *>(&stage[l32 * SLD + cl]) = d;
+            }
+        m = fminf(m, __shfl_xor(m, 32, WAVE));   // the other half holds the other 32 centroids
+        if (h == 0 && q < nq && blk < nb) bm[q * nb + blk] = m;
+        wave_sync();
+        // out again with 16 lanes per query row: every store instruction writes four rows of 256 contiguous bytes
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int r = it * 4 + sr;
+            const int64_t qq = q0 + wq + i * 32 + r, c = c0 + wc + sc;
+            const float4 d = *reinterpret_cast<const float4 *>(&stage[r * SLD + sc]);
+            if (qq < nq) {
+                float *rowp = Dt + qq * K;
+                if (vec && c + 3 < K) {
+                    *reinterpret_cast<float4 *>(rowp + c) = d;
                 } else {
                     const float dv[4] = {d.x, d.y, d.z, d.w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (c + e < K) {
-                            m = fminf(m, dv[e]);
-                            if (q < nq) rowp[c + e] = dv[e];
-                        }
+                        if (c + e < K) rowp[c + e] = dv[e];
                 }
             }
-        m = fminf(m, __shfl_xor(m, 32, WAVE));   // the other half holds the other 32 centroids
-        if (h == 0 && q < nq && blk < nb) bm[q * nb + blk] = m;
+        }
+        wave_sync();
     }
 }
 
