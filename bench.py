@@ -70,6 +70,7 @@ def main():
     ap.add_argument("--workload", default=os.environ.get("IVF_BENCH_WORKLOAD", "deep1b"))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scratch-gib", type=float, default=48.0)
+    ap.add_argument("--nq", type=int, default=0, help="use only the first NQ queries of the workload (latency runs)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run the plain 1 GiB copy kernel (reference for rocprofv3 HBM counters)")
     args = ap.parse_args()
@@ -86,6 +87,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
     spec = sd.WORKLOADS[args.workload]
+    if args.nq:
+        import dataclasses
+        spec = dataclasses.replace(spec, nq=min(args.nq, spec.nq))
     ivf.load_library()
 
     t0 = time.time()

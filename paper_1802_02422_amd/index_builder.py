@@ -74,9 +74,14 @@ def neighbour_table(centroids: torch.Tensor, L: int):
     far = d.argmax(dim=1)
     is_self[none, far[none]] = True
     d = d.masked_fill(is_self, float("inf"))
-    order = torch.sort(d, dim=1, stable=True)[1][:, :L]          # ids ascend, so stable = (distance, id)
-    nbr = torch.gather(ids, 1, order).contiguous()
-    cs = torch.gather(d, 1, order).contiguous()
+    # order every row by (distance, id) with ONE flat stable radix sort: key = row << 32 | bits(distance)
+    # (non-negative floats order like their bit patterns; ids already ascend inside a row)
+    rows = torch.arange(K, device=centroids.device, dtype=torch.int64)[:, None]
+    key = (rows << 32) | d.contiguous().view(torch.int32).to(torch.int64)
+    order = torch.sort(key.view(-1), stable=True)[1].view(K, L + 1)[:, :L]
+    del key
+    nbr = ids.view(-1)[order].contiguous()
+    cs = d.view(-1)[order].contiguous()
     return nbr, cs
 
 
