@@ -195,6 +195,119 @@ __global__ __launch_bounds__(256) void coarse_gemm_kernel(
     }
 }
 
+// The same for small batches (latency mode): a workgroup takes 32 queries x 256 centroids, all
+// four wavefronts share the 32 queries and each owns 64 of the centroids (two accumulators),
+// so a batch of up to 32 queries costs a quarter of the MFMA work of the 128-query tile and
+// the kernel is bounded by streaming the centroid matrix once per 32 queries.
+constexpr int SKQ = 32, SKC = 256;
+
+__global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
+    const float *__restrict__ Q, const float *__restrict__ qn, int64_t nq,
+    const float *__restrict__ C, const float *__restrict__ cn, int64_t K, int D,
+    float *__restrict__ Dt, float *__restrict__ bm, int nb, int tiles_q)
+{
+    __shared__ __attribute__((aligned(16))) float ops[(SKQ + SKC) * GLD];   // operands; reused as output staging
+    __shared__ __attribute__((aligned(16))) float cns[SKC];
+    static_assert(4 * 32 * SLD <= (SKQ + SKC) * GLD, "the four staging areas must fit the operand buffers");
+    float *As = ops, *Bs = ops + SKQ * GLD;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int64_t q0 = (int64_t)(blockIdx.x % tiles_q) * SKQ, c0 = (int64_t)(blockIdx.x / tiles_q) * SKC;
+    const int wc = wave * 64;
+    const int l32 = lane & 31, h = lane >> 5;
+    cns[tid] = c0 + tid < K ? cn[c0 + tid] : 0.f;
+    floatx16 acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+    float4 pa, pb[8];
+    auto fetch = [&](int k0) {
+        const int c4 = (tid & 7) * 4;
+        pa = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k0 + c4 < D && q0 + (tid >> 3) < nq)
+            pa = *reinterpret_cast<const float4 *>(Q + (q0 + (tid >> 3)) * D + k0 + c4);
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int row = (tid >> 3) + it * 32;
+            pb[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k0 + c4 < D && c0 + row < K)
+                pb[it] = *reinterpret_cast<const float4 *>(C + (c0 + row) * D + k0 + c4);
+        }
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < D; k0 += GKC) {
+        const int c4 = (tid & 7) * 4;
+        *reinterpret_cast<float4 *>(&As[(tid >> 3) * GLD + c4]) = pa;
+#pragma unroll
+        for (int it = 0; it < 8; ++it)
+            *reinterpret_cast<float4 *>(&Bs[((tid >> 3) + it * 32) * GLD + c4]) = pb[it];
+        __syncthreads();
+        if (k0 + GKC < D) fetch(k0 + GKC);
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+            const float4 a = *reinterpret_cast<const float4 *>(&As[l32 * GLD + h * 16 + s4 * 4]);
+            float4 b[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                b[j] = *reinterpret_cast<const float4 *>(&Bs[(wc + j * 32 + l32) * GLD + h * 16 + s4 * 4]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const float av = e == 0 ? a.x : e == 1 ? a.y : e == 2 ? a.z : a.w;
+                    const float bv = e == 0 ? b[j].x : e == 1 ? b[j].y : e == 2 ? b[j].z : b[j].w;
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av, acc[j], 0, 0, 0);
+                }
+        }
+        __syncthreads();
+    }
+    const bool vec = (K & 3) == 0;
+    const int64_t blk = (c0 + wc) / BMW;
+    float *stage = ops + wave * (32 * SLD);
+    const int sr = lane >> 4, sc = (lane & 15) * 4;
+    const int64_t q = q0 + l32;
+    const float qr = q < nq ? qn[q] : 0.f;
+    float m = INFINITY;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int cl = j * 32 + 8 * g + 4 * h;
+            const int64_t c = c0 + wc + cl;
+            const float4 cv = *reinterpret_cast<const float4 *>(&cns[wc + cl]);
+            float4 d;
+            d.x = fmaxf(fmaf(-2.f, acc[j][4 * g + 0], qr + cv.x), 0.f);
+            d.y = fmaxf(fmaf(-2.f, acc[j][4 * g + 1], qr + cv.y), 0.f);
+            d.z = fmaxf(fmaf(-2.f, acc[j][4 * g + 2], qr + cv.z), 0.f);
+            d.w = fmaxf(fmaf(-2.f, acc[j][4 * g + 3], qr + cv.w), 0.f);
+            m = fminf(m, c + 0 < K ? d.x : INFINITY);
+            m = fminf(m, c + 1 < K ? d.y : INFINITY);
+            m = fminf(m, c + 2 < K ? d.z : INFINITY);
+            m = fminf(m, c + 3 < K ? d.w : INFINITY);
+            *reinterpret_cast<float4 *>(&stage[l32 * SLD + cl]) = d;
+        }
+    m = fminf(m, __shfl_xor(m, 32, WAVE));
+    if (h == 0 && q < nq && blk < nb) bm[q * nb + blk] = m;
+    wave_sync();
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        const int r = it * 4 + sr;
+        const int64_t qq = q0 + r, c = c0 + wc + sc;
+        const float4 d = *reinterpret_cast<const float4 *>(&stage[r * SLD + sc]);
+        if (qq < nq) {
+            float *rowp = Dt + qq * K;
+            if (vec && c + 3 < K) {
+                *reinterpret_cast<float4 *>(rowp + c) = d;
+            } else {
+                const float dv[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (c + e < K) rowp[c + e] = dv[e];
+            }
+        }
+    }
+}
+
 // Nearest centroid only (P = 1): the same tile product, reduced on the fly to
 // the per-query minimum of (distance, centroid id), merged across centroid
 // tiles with a 64-bit atomic minimum; no distance tile is written.  best[]

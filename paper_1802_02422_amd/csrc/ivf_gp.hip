@@ -98,6 +98,13 @@ int launch_coarse(const float *x, const float *xn, int64_t nq, const float *C, c
                   int64_t K, int D, float *Dt, float *bm, hipStream_t st)
 {
     const int nb = (int)((K + BMW - 1) / BMW);
+    if (nq <= 2 * SKQ) {   // small batch: 32-query tiles
+        int tiles_q = (int)((nq + SKQ - 1) / SKQ);
+        int64_t grid = tiles_q * ((K + SKC - 1) / SKC);
+        coarse_gemm_skinny_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(x, xn, nq, C, cn, K, D, Dt, bm, nb, tiles_q);
+        LAUNCHCHK("coarse_gemm_skinny_kernel");
+        return IVF_OK;
+    }
     int tiles_q = (int)((nq + GT - 1) / GT);
     int64_t tiles_c = (K + GT - 1) / GT;
     int64_t grid = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * tiles_c;
