@@ -148,9 +148,10 @@ constexpr int SCAN_CHUNK = WAVE * SCAN_U;     // records a wavefront has in flig
 
 // Per-wavefront LDS staging of a batch of 64 descriptors.
 struct WaveStage {
+    // the batch's non-empty descriptors, compacted in order:
     uint4 a[WAVE];              // address of the codes (lo, hi), address of the constant bytes (lo, hi)
     uint4 b[WAVE];              // first flattened record index, len, base (bits), pos0
-    uint8_t mark[SCAN_CHUNK];   // 1 + lane of the descriptor whose first record sits here, else 0
+    uint8_t mark[SCAN_CHUNK];   // 1 where the first record of a descriptor sits, else 0
 };
 static_assert(SCAN_CHUNK % 16 == 0 && sizeof(WaveStage) % 16 == 0, "stage arrays must stay 16-byte aligned");
 
@@ -173,22 +174,24 @@ __device__ __forceinline__ void scan_issue(ChunkRegs<M> &r, WaveStage &st, uint3
 #pragma unroll
     for (int i = lane; i < SCAN_CHUNK / 4; i += WAVE) reinterpret_cast<uint32_t *>(st.mark)[i] = 0u;
     wave_sync();
-    if (len > 0 && pre >= t0 && pre - t0 < (uint32_t)SCAN_CHUNK) st.mark[pre - t0] = (uint8_t)(lane + 1);
+    if (len > 0 && pre >= t0 && pre - t0 < (uint32_t)SCAN_CHUNK) st.mark[pre - t0] = 1;
     wave_sync();
-    uint32_t sc[SCAN_U], tot[SCAN_U];
+    // The owner of record t is the descriptor whose head is the last one at or before t.  The
+    // stage holds the non-empty descriptors in order, so its slot is (number of heads at or
+    // before t) - 1: heads before this 64-record step (carry, wave-uniform), plus heads at
+    // lower lanes of the step (population count of the ballot below the lane), plus its own.
+    uint32_t head[SCAN_U];
 #pragma unroll
-    for (int u = 0; u < SCAN_U; ++u) sc[u] = (uint32_t)st.mark[WAVE * u + lane];
-#pragma unroll
-    for (int u = 0; u < SCAN_U; ++u) sc[u] = wave_inclusive_max_scan(sc[u]);   // four independent chains
-#pragma unroll
-    for (int u = 0; u < SCAN_U; ++u) tot[u] = (uint32_t)__builtin_amdgcn_readlane((int)sc[u], WAVE - 1);
+    for (int u = 0; u < SCAN_U; ++u) head[u] = (uint32_t)st.mark[WAVE * u + lane];
 #pragma unroll
     for (int u = 0; u < SCAN_U; ++u) {
         const uint32_t t = t0 + WAVE * u + lane;
-        const uint32_t o = sc[u] > carry ? sc[u] : carry;
-        carry = tot[u] > carry ? tot[u] : carry;
+        const uint64_t hm = __ballot(head[u] != 0);
+        const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(hm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hm, 0u));
+        const uint32_t o = carry + below + head[u];
+        carry += (uint32_t)__popcll(hm);
         bool act = t < T && o > 0;
-        const uint32_t oi = act ? o - 1 : 0;
+        const uint32_t oi = act ? (o - 1) & (WAVE - 1) : 0;   // always inside the stage
         const uint4 db = st.b[oi];
         const uint32_t c = t - db.x;
         act = act && c < db.y;                     // never read outside the owner's block
@@ -210,8 +213,8 @@ __device__ __forceinline__ void scan_issue(ChunkRegs<M> &r, WaveStage &st, uint3
 // the query's S descriptors, each wavefront batches of 64 of them.  The
 // records of a batch are flattened: a prefix sum of the lengths numbers them,
 // every lane takes record t = t0 + 64u + lane of the current chunk, and finds
-// the owning descriptor from head marks in LDS by a running maximum across
-// the lanes (DPP).  All lanes are busy whatever the subregion lengths, a
+// the owning descriptor from head marks in LDS by counting the heads before it
+// (ballot + population count).  All lanes are busy whatever the subregion lengths, a
 // 16-byte code is one 128-bit load, and the loads of the next chunk are issued
 // before the table lookups of the current one, so each wavefront keeps two
 // chunks (about 8 KB) in flight.  The M bytes index the query's table in LDS;
@@ -287,8 +290,12 @@ __global__ __launch_bounds__(SCAN_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4
             wave_sync();
             const uint64_t pc = reinterpret_cast<uint64_t>(blocks) + (uint64_t)sd.blk * 64u;
             const uint64_t pb = pc + (uint64_t)len * M;
-            st.a[lane] = make_uint4((uint32_t)pc, (uint32_t)(pc >> 32), (uint32_t)pb, (uint32_t)(pb >> 32));
-            st.b[lane] = make_uint4(pre, len, __float_as_uint(sd.base), sd.pos0);
+            const uint64_t ne = __ballot(len > 0);
+            const uint32_t slot = __builtin_amdgcn_mbcnt_hi((uint32_t)(ne >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ne, 0u));
+            if (len > 0) {
+                st.a[slot] = make_uint4((uint32_t)pc, (uint32_t)(pc >> 32), (uint32_t)pb, (uint32_t)(pb >> 32));
+                st.b[slot] = make_uint4(pre, len, __float_as_uint(sd.base), sd.pos0);
+            }
         }
         scan_issue<M>(r, st, t_next, Tn, len, pre, carry);
         t_next += SCAN_CHUNK;
