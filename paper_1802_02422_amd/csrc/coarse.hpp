@@ -30,9 +30,10 @@ constexpr int GLD = GKC + 4;   // LDS row stride in floats (keeps 16-byte alignm
 
 // One 128x128 tile of <Q[q], C[j]> per workgroup of 4 wavefronts; each
 // wavefront owns a 64x64 quadrant as 2x2 v_mfma_f32_32x32x2f32 accumulators.
-// Within a 32-dim stage lane half h feeds dims [16h, 16h+16) to both operands,
-// so one ds_read_b128 serves four MFMA steps (the order of the k-summation is
-// free).  The centroids are the MFMA's row operand and the queries its column
+// Within each 16-dim half of a 32-dim stage lane half h feeds dims [8h, 8h+8) to
+// both operands, so one ds_read_b128 serves four MFMA steps (the order of the
+// k-summation is free; all variants of the kernel use the same one, so a query's
+// distances do not depend on the batch it arrives in).  The centroids are the MFMA's row operand and the queries its column
 // operand: in acc[i][j], lane l holds query (column) wq + 32i + l%32 and element
 // v is centroid (row) wc + 32j + 8*(v/4) + 4*(l/32) + v%4, i.e. four groups of
 // four consecutive centroids, which the epilogues store as 128-bit words and
@@ -59,11 +60,16 @@ __device__ __forceinline__ void gemm_tile(const float *__restrict__ Q, int64_t n
         for (int it = 0; it < 4; ++it) {
             int idx = tid + it * 256;
             int row = idx >> 3, c4 = (idx & 7) * 4;
-            pa[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-            pb[it] = pa[it];
-            if (k0 + c4 < D) {
-                if (q0 + row < nq) pa[it] = *reinterpret_cast<const float4 *>(Q + (q0 + row) * D + k0 + c4);
-                if (c0 + row < K) pb[it] = *reinterpret_cast<const float4 *>(C + (c0 + row) * D + k0 + c4);
+            // rows past the end are clamped to the last row (their products are never stored), columns
+            // past D read column 0 and are zeroed: every load is unconditional
+            const bool kv = k0 + c4 < D;
+            const int64_t qrow = q0 + row < nq ? q0 + row : nq - 1, crow = c0 + row < K ? c0 + row : K - 1;
+            const int col = kv ? k0 + c4 : 0;
+            pa[it] = *reinterpret_cast<const float4 *>(Q + qrow * D + col);
+            pb[it] = *reinterpret_cast<const float4 *>(C + crow * D + col);
+            if (!kv) {
+                pa[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+                pb[it] = pa[it];
             }
         }
     };
@@ -83,8 +89,10 @@ __device__ __forceinline__ void gemm_tile(const float *__restrict__ Q, int64_t n
             float4 a[2], b[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                a[i] = *reinterpret_cast<const float4 *>(&As[(wq + i * 32 + l32) * GLD + h * 16 + s4 * 4]);
-                b[i] = *reinterpret_cast<const float4 *>(&Bs[(wc + i * 32 + l32) * GLD + h * 16 + s4 * 4]);
+                // same k order as the DMA variant: sub-stages of 16 dims, lane half h feeds [8h, 8h+8)
+                const int kc = (s4 >> 1) * 16 + h * 8 + (s4 & 1) * 4;
+                a[i] = *reinterpret_cast<const float4 *>(&As[(wq + i * 32 + l32) * GLD + kc]);
+                b[i] = *reinterpret_cast<const float4 *>(&Bs[(wc + i * 32 + l32) * GLD + kc]);
             }
             // the four accumulators are independent: cycle through them so that no MFMA
             // waits for the one issued just before it
@@ -123,14 +131,96 @@ __device__ __forceinline__ bool tile_of_block(int64_t b, int tiles_q, int64_t &q
 // Dt[q][j] = max(0, qn[q] + cn[j] - 2 <Q[q], C[j]>), and bm[q][b] = the minimum
 // of Dt[q][64b .. 64b+63] (each wavefront's 64-centroid quadrant gives one block
 // minimum per query).  The grid has 8 * ceil(tiles_q / 8) * tiles_c workgroups.
+// The same tile product with asynchronous operand staging, for D a multiple of 16: stages of
+// 16 dims, operands copied global -> LDS by global_load_lds_dwordx4 (no registers, no ds_write),
+// two LDS buffers so that the copy of stage s+1 runs under the MFMA block of stage s with one
+// barrier per stage.  A direct-to-LDS load puts lane i's 16 bytes at base + 16 i, so the layout
+// is unpadded rows of four float4; bank conflicts of the operand reads are avoided by storing
+// float4 f of row r in slot f ^ ((r >> 2) & 3) (each lane simply fetches the float4 that belongs
+// to its slot).  Lane half h feeds dims [8h, 8h+8) of the stage.  buf holds 2 x (128 + 128) rows
+// x 16 floats.
+constexpr int DK = 16;                       // dims per stage
+constexpr int DBUF = 2 * GT * DK;            // floats per buffer (A rows then B rows)
+
+__device__ __forceinline__ void gemm_tile_dma(const float *__restrict__ Q, int64_t nq, int64_t q0,
+                                              const float *__restrict__ C, int64_t K, int64_t c0, int D,
+                                              float *buf, floatx16 (&acc)[2][2])
+{
+    typedef const __attribute__((address_space(1))) void *gptr_t;
+    typedef __attribute__((address_space(3))) void *lptr_t;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wq = (wave >> 1) * 64, wc = (wave & 1) * 64;
+    const int l32 = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // this wave's four copy instructions per stage: blocks of 16 rows; blocks 0-7 are query rows,
+    // 8-15 centroid rows.  Rows past the end are clamped (their products are never stored).
+    const float *src[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        const int blk = wave * 4 + n;
+        const int r = (blk & 7) * 16 + (lane >> 2);                    // row inside the operand tile
+        const int f = (lane & 3) ^ ((r >> 2) & 3);                     // float4 of the row this slot holds
+        if (blk < 8) {
+            const int64_t row = q0 + r < nq ? q0 + r : nq - 1;
+            src[n] = Q + row * D + f * 4;
+        } else {
+            const int64_t row = c0 + r < K ? c0 + r : K - 1;
+            src[n] = C + row * D + f * 4;
+        }
+    }
+    auto issue = [&](int k0, float *dst) {
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+            __builtin_amdgcn_global_load_lds((gptr_t)(src[n] + k0), (lptr_t)(dst + (wave * 4 + n) * 256), 16, 0, 0);
+    };
+    const int stages = D / DK;
+    issue(0, buf);
+    for (int s = 0; s < stages; ++s) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's copies of stage s have landed
+        __syncthreads();                      // ... and everyone's; all waves are done with the other buffer
+        if (s + 1 < stages) issue((s + 1) * DK, buf + ((s + 1) & 1) * DBUF);
+        const float *As = buf + (s & 1) * DBUF, *Bs = As + GT * DK;
+#pragma unroll
+        for (int s4 = 0; s4 < 2; ++s4) {
+            float4 a[2], b[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int ra = wq + i * 32 + l32, rb = wc + i * 32 + l32;
+                a[i] = *reinterpret_cast<const float4 *>(&As[ra * DK + (((2 * h + s4) ^ ((ra >> 2) & 3)) << 2)]);
+                b[i] = *reinterpret_cast<const float4 *>(&Bs[rb * DK + (((2 * h + s4) ^ ((rb >> 2) & 3)) << 2)]);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const float av = e == 0 ? a[i].x : e == 1 ? a[i].y : e == 2 ? a[i].z : a[i].w;
+                        const float bv = e == 0 ? b[j].x : e == 1 ? b[j].y : e == 2 ? b[j].z : b[j].w;
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av, acc[i][j], 0, 0, 0);
+                    }
+        }
+    }
+    __syncthreads();   // operands are dead: the buffers may be reused
+}
+
 constexpr int SLD = 64 + 4;   // row stride (floats) of a wavefront's 32x64 output staging area in LDS
 
-__global__ __launch_bounds__(256) void coarse_gemm_kernel(
+template <bool DMA>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void coarse_gemm_kernel(
     const float *__restrict__ Q, const float *__restrict__ qn, int64_t nq,
     const float *__restrict__ C, const float *__restrict__ cn, int64_t K, int D,
     float *__restrict__ Dt, float *__restrict__ bm, int nb, int tiles_q)
 {
-    __shared__ __attribute__((aligned(16))) float ops[2 * GT * GLD];   // operands; reused as output staging
+    // operands (register-staged: two padded 128x32 tiles; DMA: two buffers of 256x16), reused as output staging
+    __shared__ __attribute__((aligned(16))) float ops[DMA ? 4 * 32 * SLD : 2 * GT * GLD];
+    static_assert(2 * DBUF <= 4 * 32 * SLD, "the DMA buffers must fit the staging area");
     __shared__ __attribute__((aligned(16))) float cns[GT];
     static_assert(4 * 32 * SLD <= 2 * GT * GLD, "the four staging areas must fit the operand buffers");
     float *As = ops, *Bs = ops + GT * GLD;
@@ -141,7 +231,9 @@ __global__ __launch_bounds__(256) void coarse_gemm_kernel(
     const int l32 = lane & 31, h = lane >> 5;
     if (threadIdx.x < GT) cns[threadIdx.x] = c0 + threadIdx.x < K ? cn[c0 + threadIdx.x] : 0.f;
     floatx16 acc[2][2];
-    gemm_tile(Q, nq, q0, C, K, c0, D, As, Bs, acc);   // ends with a barrier: cns is visible, operands are dead
+    // both end with a barrier: cns is visible, operands are dead
+    if (DMA) gemm_tile_dma(Q, nq, q0, C, K, c0, D, ops, acc);
+    else gemm_tile(Q, nq, q0, C, K, c0, D, As, Bs, acc);
     const bool vec = (K & 3) == 0;
     const int64_t blk = (c0 + wc) / BMW;
     float *stage = ops + wave * (32 * SLD);
@@ -245,11 +337,12 @@ __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
         if (k0 + GKC < D) fetch(k0 + GKC);
 #pragma unroll
         for (int s4 = 0; s4 < 4; ++s4) {
-            const float4 a = *reinterpret_cast<const float4 *>(&As[l32 * GLD + h * 16 + s4 * 4]);
+            const int kc = (s4 >> 1) * 16 + h * 8 + (s4 & 1) * 4;   // same k order as the other variants
+            const float4 a = *reinterpret_cast<const float4 *>(&As[l32 * GLD + kc]);
             float4 b[2];
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                b[j] = *reinterpret_cast<const float4 *>(&Bs[(wc + j * 32 + l32) * GLD + h * 16 + s4 * 4]);
+                b[j] = *reinterpret_cast<const float4 *>(&Bs[(wc + j * 32 + l32) * GLD + kc]);
 #pragma unroll
             for (int e = 0; e < 4; ++e)
 #pragma unroll

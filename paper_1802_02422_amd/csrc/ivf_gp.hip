@@ -109,7 +109,10 @@ int launch_coarse(const float *x, const float *xn, int64_t nq, const float *C, c
     int64_t tiles_c = (K + GT - 1) / GT;
     int64_t grid = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * tiles_c;
     if (grid >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
-    coarse_gemm_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(x, xn, nq, C, cn, K, D, Dt, bm, nb, tiles_q);
+    if (D % DK == 0)
+        coarse_gemm_kernel<true><<<dim3((unsigned)grid), dim3(256), 0, st>>>(x, xn, nq, C, cn, K, D, Dt, bm, nb, tiles_q);
+    else
+        coarse_gemm_kernel<false><<<dim3((unsigned)grid), dim3(256), 0, st>>>(x, xn, nq, C, cn, K, D, Dt, bm, nb, tiles_q);
     LAUNCHCHK("coarse_gemm_kernel");
     return IVF_OK;
 }
