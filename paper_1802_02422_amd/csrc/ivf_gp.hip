@@ -138,7 +138,7 @@ struct ivf_index {
     float *centroids = nullptr, *cnorm = nullptr, *alpha = nullptr, *cst = nullptr;
     float *codebook = nullptr, *const_table = nullptr;
     int32_t *nbr = nullptr, *ids = nullptr;
-    uint32_t *sub_offsets = nullptr, *blk_off = nullptr;
+    uint4 *sub_info = nullptr;   // per subregion: block offset, first position, length
     uint8_t *blocks = nullptr;
     int64_t scratch_limit = 8ll << 30;
     Buf dt, bm, qn, probe_id, probe_d, desc, lut, partial;
@@ -164,7 +164,7 @@ extern "C" void ivf_free_index(ivf_index *ix)
     if (!ix) return;
     (void)hipDeviceSynchronize();
     void *owned[] = {ix->centroids, ix->cnorm, ix->alpha, ix->cst, ix->codebook, ix->const_table,
-                     ix->nbr, ix->ids, ix->sub_offsets, ix->blk_off, ix->blocks, ix->dt.p, ix->bm.p, ix->qn.p,
+                     ix->nbr, ix->ids, ix->sub_info, ix->blocks, ix->dt.p, ix->bm.p, ix->qn.p,
                      ix->probe_id.p, ix->probe_d.p, ix->desc.p, ix->lut.p, ix->partial.p};
     for (void *p : owned)
         if (p) (void)hipFree(p);
@@ -201,7 +201,6 @@ int load_impl(const ivf_index_desc *d, hipStream_t st, ivf_index *ix)
     if ((rc = dev_copy(ix->alpha, d->alpha, (size_t)K, st))) return rc;
     if ((rc = dev_copy(ix->codebook, d->pq_codebook, (size_t)256 * D, st))) return rc;
     if ((rc = dev_copy(ix->const_table, d->const_table, (size_t)256, st))) return rc;
-    if ((rc = dev_copy(ix->sub_offsets, d->sub_offsets, (size_t)nsub + 1, st))) return rc;
     if ((rc = dev_copy(ix->ids, d->ids, (size_t)N, st))) return rc;
 
     HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->cnorm), (size_t)K * sizeof(float)));
@@ -214,18 +213,19 @@ int load_impl(const ivf_index_desc *d, hipStream_t st, ivf_index *ix)
     // block offsets: exclusive prefix sum of the block sizes
     uint32_t *sz = nullptr;
     HIPCHK(hipMalloc(reinterpret_cast<void **>(&sz), (size_t)nsub * sizeof(uint32_t)));
-    HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->blk_off), (size_t)nsub * sizeof(uint32_t)));
-    blk_size_kernel<<<dim3((unsigned)((nsub + 255) / 256)), dim3(256), 0, st>>>(ix->sub_offsets, nsub, M, sz);
+    uint32_t *blk_off = nullptr;
+    HIPCHK(hipMalloc(reinterpret_cast<void **>(&blk_off), (size_t)nsub * sizeof(uint32_t)));
+    blk_size_kernel<<<dim3((unsigned)((nsub + 255) / 256)), dim3(256), 0, st>>>(d->sub_offsets, nsub, M, sz);
     LAUNCHCHK("blk_size_kernel");
     size_t tmp_bytes = 0;
-    HIPCHK(rocprim::exclusive_scan(nullptr, tmp_bytes, sz, ix->blk_off, 0u, (size_t)nsub,
+    HIPCHK(rocprim::exclusive_scan(nullptr, tmp_bytes, sz, blk_off, 0u, (size_t)nsub,
                                    rocprim::plus<uint32_t>(), st));
     void *tmp = nullptr;
     HIPCHK(hipMalloc(&tmp, tmp_bytes ? tmp_bytes : 16));
-    HIPCHK(rocprim::exclusive_scan(tmp, tmp_bytes, sz, ix->blk_off, 0u, (size_t)nsub,
+    HIPCHK(rocprim::exclusive_scan(tmp, tmp_bytes, sz, blk_off, 0u, (size_t)nsub,
                                    rocprim::plus<uint32_t>(), st));
     uint32_t last_off = 0, last_sz = 0;
-    HIPCHK(hipMemcpyAsync(&last_off, ix->blk_off + nsub - 1, 4, hipMemcpyDeviceToHost, st));
+    HIPCHK(hipMemcpyAsync(&last_off, blk_off + nsub - 1, 4, hipMemcpyDeviceToHost, st));
     HIPCHK(hipMemcpyAsync(&last_sz, sz + nsub - 1, 4, hipMemcpyDeviceToHost, st));
     HIPCHK(hipStreamSynchronize(st));
     uint64_t total_blk = (uint64_t)last_off + last_sz;
@@ -236,9 +236,13 @@ int load_impl(const ivf_index_desc *d, hipStream_t st, ivf_index *ix)
     HIPCHK(hipFree(sz));
     HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->blocks), (size_t)(total_blk ? total_blk : 1) * BLK_ALIGN));
     repack_kernel<<<dim3((unsigned)((nsub * 16 + 255) / 256)), dim3(256), 0, st>>>(
-        ix->sub_offsets, ix->blk_off, nsub, M, d->codes, d->const_byte, ix->blocks);
+        d->sub_offsets, blk_off, nsub, M, d->codes, d->const_byte, ix->blocks);
     LAUNCHCHK("repack_kernel");
+    HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->sub_info), (size_t)nsub * sizeof(uint4)));
+    sub_info_kernel<<<dim3((unsigned)((nsub + 255) / 256)), dim3(256), 0, st>>>(d->sub_offsets, blk_off, nsub, ix->sub_info);
+    LAUNCHCHK("sub_info_kernel");
     HIPCHK(hipStreamSynchronize(st));
+    HIPCHK(hipFree(blk_off));
     return IVF_OK;
 }
 
@@ -360,10 +364,10 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
         int64_t *ns = n_scanned_out ? n_scanned_out + q0 : nullptr;
         if (PL > 4096)
             score_prune_kernel<1024><<<dim3((unsigned)n), dim3(1024), sp_lds, st>>>(
-                Dt, K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_offsets, ix->blk_off, desc, ks, ns);
+                Dt, K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, desc, ks, ns);
         else
             score_prune_kernel<256><<<dim3((unsigned)n), dim3(256), sp_lds, st>>>(
-                Dt, K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_offsets, ix->blk_off, desc, ks, ns);
+                Dt, K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, desc, ks, ns);
         LAUNCHCHK("score_prune_kernel");
         if ((rc = mark(3))) return rc;
         if ((rc = mark(4))) return rc;

@@ -51,6 +51,18 @@ __global__ __launch_bounds__(256) void repack_kernel(
     }
 }
 
+// one record per subregion with everything the pruning stage needs to describe it to the scan:
+// block offset (64-byte units), first grouped position, length
+__global__ __launch_bounds__(256) void sub_info_kernel(const uint32_t *__restrict__ sub_offsets,
+                                                       const uint32_t *__restrict__ blk_off, int64_t nsub,
+                                                       uint4 *__restrict__ info)
+{
+    int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (b >= nsub) return;
+    uint32_t p0 = sub_offsets[b];
+    info[b] = make_uint4(blk_off[b], p0, sub_offsets[b + 1] - p0, 0u);
+}
+
 // plain streaming copy of n16 16-byte words (reference point for HBM counters and timings)
 __global__ __launch_bounds__(256) void copy_bytes_kernel(const uint4 *__restrict__ src,
                                                          uint4 *__restrict__ dst, int64_t n16)

@@ -27,7 +27,7 @@ __global__ __launch_bounds__(BLOCK) void score_prune_kernel(
     const float *__restrict__ Dt, int64_t K, const int32_t *__restrict__ probe_id,
     const float *__restrict__ probe_d, int P, int L, const int32_t *__restrict__ nbr,
     const float *__restrict__ cst, const float *__restrict__ alpha, int S,
-    const uint32_t *__restrict__ sub_offsets, const uint32_t *__restrict__ blk_off,
+    const uint4 *__restrict__ sub_info,
     SubDesc *__restrict__ desc, int64_t *__restrict__ kept_sub, int64_t *__restrict__ n_scanned)
 {
     __shared__ SelectShared sh;
@@ -64,11 +64,11 @@ __global__ __launch_bounds__(BLOCK) void score_prune_kernel(
     block_emit_selected<BLOCK>(key, PL, (uint32_t)S, pivot, need, sh,
                                [&](uint32_t pos, int64_t i, uint32_t k) {
                                    const int64_t b = (int64_t)pid[i / L] * L + (i % L);
-                                   const uint32_t p0 = sub_offsets[b], p1 = sub_offsets[b + 1];
+                                   const uint4 info = sub_info[b];   // one 16-byte read per kept subregion
                                    SubDesc d;
-                                   d.blk = blk_off[b];
-                                   d.pos0 = p0;
-                                   d.len = p1 - p0;
+                                   d.blk = info.x;
+                                   d.pos0 = info.y;
+                                   d.len = info.z;
                                    d.base = key_float(k);
                                    desc[q * S + pos] = d;
                                    if (kept_sub) kept_sub[q * S + pos] = b;
