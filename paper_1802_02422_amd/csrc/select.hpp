@@ -98,6 +98,39 @@ __device__ uint32_t block_emit_selected(KeyFn key, int64_t n, uint32_t nsel, uin
     return run_lt + (run_eq < need ? run_eq : need);
 }
 
+// The same selection for keys that are cheap to re-read (LDS): every thread owns a contiguous
+// run of ceil(n / BLOCK) items, counts its selected ones, one workgroup scan turns the counts
+// into output offsets, and the thread then emits its run in order.  One scan instead of one
+// per BLOCK items.  n < 65536.
+template <int BLOCK, class KeyFn, class EmitFn>
+__device__ uint32_t block_emit_selected_runs(KeyFn key, int n, uint32_t pivot, uint32_t need,
+                                             SelectShared &sh, EmitFn emit)
+{
+    const int ipt = (n + BLOCK - 1) / BLOCK;
+    const int i0 = threadIdx.x * ipt, i1 = i0 + ipt < n ? i0 + ipt : n;
+    uint32_t lt = 0, eq = 0;
+    for (int i = i0; i < i1; ++i) {
+        const uint32_t k = key(i);
+        lt += k < pivot;
+        eq += k == pivot;
+    }
+    uint32_t total;
+    const uint32_t exc = block_exclusive_scan<BLOCK>(lt | (eq << 16), sh.scan, total);
+    uint32_t lt_seen = exc & 0xFFFFu, eq_seen = exc >> 16;
+    for (int i = i0; i < i1; ++i) {
+        const uint32_t k = key(i);
+        if (k < pivot) {
+            emit(lt_seen + (eq_seen < need ? eq_seen : need), (int64_t)i, k);
+            ++lt_seen;
+        } else if (k == pivot) {
+            if (eq_seen < need) emit(lt_seen + eq_seen, (int64_t)i, k);
+            ++eq_seen;
+        }
+    }
+    const uint32_t tl = total & 0xFFFFu, te = total >> 16;
+    return tl + (te < need ? te : need);
+}
+
 // In-place ascending bitonic sort of n (a power of two) uint64 keys in LDS by
 // the whole workgroup.
 template <int BLOCK>
