@@ -1,12 +1,24 @@
 // Stage 1: squared distances from a tile of queries to all K centroids as an
-// fp32 MFMA GEMM (||q||^2 - 2<q,c> + ||c||^2), and the exact per-query
-// selection of the nprobe closest regions (exhaustive assignment, Section 3.1).
+// MFMA GEMM (||q||^2 - 2<q,c> + ||c||^2), and the exact per-query selection of
+// the nprobe closest regions (exhaustive assignment, Section 3.1).
+//
+// The inner products run on the fp16 matrix cores at fp32 accuracy: every
+// operand row is scaled by a power of two so that its largest magnitude lies in
+// [2^14, 2^15) and split into hi = fp16(x) and lo = fp16(x - hi), which
+// together carry 22 significant bits; <q,c> is accumulated in fp32 from the
+// three products lo*hi + hi*lo + hi*hi per 16 dimensions (each fp16 product is
+// exact in fp32; the dropped lo*lo term is below 2^-24 of |q_i c_i|), and the
+// scales, being powers of two, are undone exactly in the epilogue.  The
+// rounding error of a distance is that of an fp32 dot product with 18 instead
+// of 96 accumulation steps.
 #pragma once
 #include "select.hpp"
 
 namespace ivf {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef uint32_t gu32x4 __attribute__((ext_vector_type(4)));
 
 // ||row||^2 of an [n][D] fp32 matrix, one wavefront per row.
 __global__ __launch_bounds__(256) void row_norm_kernel(const float *__restrict__ X, int64_t n,
@@ -24,127 +36,104 @@ __global__ __launch_bounds__(256) void row_norm_kernel(const float *__restrict__
     if (lane == 0) out[row] = s;
 }
 
-constexpr int GT = 128;        // tile: GT queries x GT centroids per workgroup
-constexpr int GKC = 32;        // dimensions staged per step
-constexpr int GLD = GKC + 4;   // LDS row stride in floats (keeps 16-byte alignment, spreads banks)
-
-// One 128x128 tile of <Q[q], C[j]> per workgroup of 4 wavefronts; each
-// wavefront owns a 64x64 quadrant as 2x2 v_mfma_f32_32x32x2f32 accumulators.
-// Within each 16-dim half of a 32-dim stage lane half h feeds dims [8h, 8h+8) to
-// both operands, so one ds_read_b128 serves four MFMA steps (the order of the
-// k-summation is free; all variants of the kernel use the same one, so a query's
-// distances do not depend on the batch it arrives in).  The centroids are the MFMA's row operand and the queries its column
-// operand: in acc[i][j], lane l holds query (column) wq + 32i + l%32 and element
-// v is centroid (row) wc + 32j + 8*(v/4) + 4*(l/32) + v%4, i.e. four groups of
-// four consecutive centroids, which the epilogues store as 128-bit words and
-// reduce without leaving the lane.
-__device__ __forceinline__ void gemm_tile(const float *__restrict__ Q, int64_t nq, int64_t q0,
-                                          const float *__restrict__ C, int64_t K, int64_t c0, int D,
-                                          float *As, float *Bs, floatx16 (&acc)[2][2])
+// Largest magnitude of count floats, as the bit pattern of a non-negative float
+// (those order like unsigned integers); out must start at 0.
+__global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ X, int64_t count,
+                                                     uint32_t *__restrict__ out)
 {
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int wq = (wave >> 1) * 64, wc = (wave & 1) * 64;
-    const int l32 = lane & 31, h = lane >> 5;
+    float m = 0.f;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256)
+        m = fmaxf(m, fabsf(X[i]));
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    for (int o = WAVE / 2; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, WAVE));
+    if ((threadIdx.x & 63) == 0) atomicMax(out, __float_as_uint(m));
+}
 
-    // the global loads of stage s+1 are issued before the MFMA block of stage s and
-    // land in registers while it runs
-    float4 pa[4], pb[4];
-    auto fetch = [&](int k0) {
+constexpr int DK = 16;                       // dimensions per operand stage
+__host__ __device__ inline int packed_dim(int D) { return (D + DK - 1) / DK * DK; }
+
+// Operand packing for the GEMM: row r of X ([n][D] fp32) becomes packed_dim(D)/16
+// stages of 64 bytes, stage t = [hi k0..7 | lo k0..7 | hi k8..15 | lo k8..15] of
+// dimensions 16t + k (fp16, zero beyond D), scaled by s = 2^(14 - floor(log2 m)):
+// m is the row's largest magnitude, or the whole matrix's when gmax (the result
+// of absmax_kernel) is given.  Also writes ||row||^2 and 1/s (per row, or
+// inv_scale[0] for a matrix-wide scale).  One wavefront per row.
+__global__ __launch_bounds__(256) void split_rows_kernel(const float *__restrict__ X, int64_t n, int D,
+                                                         const uint32_t *__restrict__ gmax,
+                                                         _Float16 *__restrict__ P, float *__restrict__ norm,
+                                                         float *__restrict__ inv_scale)
+{
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= n) return;
+    const int Dp = packed_dim(D);
+    float s2 = 0.f, m = 0.f;
+    for (int i = lane; i < D; i += WAVE) {
+        const float v = X[row * D + i];
+        s2 = fmaf(v, v, s2);
+        m = fmaxf(m, fabsf(v));
+    }
+    s2 = wave_sum(s2);
+    if (gmax) {
+        m = __uint_as_float(*gmax);
+    } else {
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            int idx = tid + it * 256;
-            int row = idx >> 3, c4 = (idx & 7) * 4;
-            // rows past the end are clamped to the last row (their products are never stored), columns
-            // past D read column 0 and are zeroed: every load is unconditional
-            const bool kv = k0 + c4 < D;
-            const int64_t qrow = q0 + row < nq ? q0 + row : nq - 1, crow = c0 + row < K ? c0 + row : K - 1;
-            const int col = kv ? k0 + c4 : 0;
-            pa[it] = *reinterpret_cast<const float4 *>(Q + qrow * D + col);
-            pb[it] = *reinterpret_cast<const float4 *>(C + crow * D + col);
-            if (!kv) {
-                pa[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-                pb[it] = pa[it];
-            }
-        }
-    };
-    fetch(0);
-    for (int k0 = 0; k0 < D; k0 += GKC) {
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            int idx = tid + it * 256;
-            int row = idx >> 3, c4 = (idx & 7) * 4;
-            *reinterpret_cast<float4 *>(&As[row * GLD + c4]) = pa[it];
-            *reinterpret_cast<float4 *>(&Bs[row * GLD + c4]) = pb[it];
-        }
-        __syncthreads();
-        if (k0 + GKC < D) fetch(k0 + GKC);
-#pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) {
-            float4 a[2], b[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                // same k order as the DMA variant: sub-stages of 16 dims, lane half h feeds [8h, 8h+8)
-                const int kc = (s4 >> 1) * 16 + h * 8 + (s4 & 1) * 4;
-                a[i] = *reinterpret_cast<const float4 *>(&As[(wq + i * 32 + l32) * GLD + kc]);
-                b[i] = *reinterpret_cast<const float4 *>(&Bs[(wc + i * 32 + l32) * GLD + kc]);
-            }
-            // the four accumulators are independent: cycle through them so that no MFMA
-            // waits for the one issued just before it
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const float av = e == 0 ? a[i].x : e == 1 ? a[i].y : e == 2 ? a[i].z : a[i].w;
-                        const float bv = e == 0 ? b[j].x : e == 1 ? b[j].y : e == 2 ? b[j].z : b[j].w;
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av, acc[i][j], 0, 0, 0);
-                    }
-        }
-        __syncthreads();
+        for (int o = WAVE / 2; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, WAVE));
+    }
+    int e = (m > 0.f && m < INFINITY) ? ilogbf(m) : 14;
+    e = e < -100 ? -100 : e > 100 ? 100 : e;
+    const float s = ldexpf(1.f, 14 - e);
+    _Float16 *out = P + row * (int64_t)Dp * 2;
+    for (int i = lane; i < Dp; i += WAVE) {
+        const float v = i < D ? X[row * D + i] * s : 0.f;
+        const _Float16 hi = (_Float16)v;
+        const _Float16 lo = (_Float16)(v - (float)hi);
+        const int at = (i >> 4) * 32 + ((i >> 3) & 1) * 16 + (i & 7);
+        out[at] = hi;
+        out[at + 8] = lo;
+    }
+    if (lane == 0) {
+        norm[row] = s2;
+        if (!gmax) inv_scale[row] = ldexpf(1.f, e - 14);
+        else if (row == 0) inv_scale[0] = ldexpf(1.f, e - 14);
     }
 }
 
-constexpr int BMW = 64;   // centroids per block minimum
-constexpr int N_XCD = 8;  // workgroups are dealt round-robin to the 8 XCDs, each with its own L2
+constexpr int GT = 128;        // tile: GT queries x GT centroids per workgroup
+constexpr int DBUF = 2 * GT * DK;            // floats per operand buffer (A rows then B rows)
+constexpr int ROWF = DK;                     // floats (4-byte units) per packed row stage: 64 bytes
 
-// Tile of workgroup b: XCD x = b % 8 owns the query tiles x, x+8, ... (a few hundred KB that
-// stay in its L2) and sweeps the centroid tiles in order, so every XCD streams the centroid
-// matrix once and the eight of them work on the same centroid tile at about the same time.
-__device__ __forceinline__ bool tile_of_block(int64_t b, int tiles_q, int64_t &q0, int64_t &c0)
+// acc += <A row, B row> over one staged 16 dimensions for this lane's fragments:
+// a[0]/b[0] hold hi, a[1]/b[1] lo of the lane half's 8 dimensions.  The small
+// cross terms go first.  The centroids are the MFMA's row operand.
+__device__ __forceinline__ floatx16 mfma3(const gu32x4 (&bfrag)[2], const gu32x4 (&afrag)[2], floatx16 acc, int which)
 {
-    const int tq_per = (tiles_q + N_XCD - 1) / N_XCD;
-    const int xcd = (int)(b % N_XCD);
-    const int64_t local = b / N_XCD;
-    const int tq = (int)(local % tq_per) * N_XCD + xcd;
-    q0 = (int64_t)tq * GT;
-    c0 = (local / tq_per) * GT;
-    return tq < tiles_q;
+    const halfx8 bh = __builtin_bit_cast(halfx8, bfrag[0]), bl = __builtin_bit_cast(halfx8, bfrag[1]);
+    const halfx8 ah = __builtin_bit_cast(halfx8, afrag[0]), al = __builtin_bit_cast(halfx8, afrag[1]);
+    if (which == 0) return __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, ah, acc, 0, 0, 0);
+    if (which == 1) return __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, al, acc, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, ah, acc, 0, 0, 0);
 }
 
-// Dt[q][j] = max(0, qn[q] + cn[j] - 2 <Q[q], C[j]>), and bm[q][b] = the minimum
-// of Dt[q][64b .. 64b+63] (each wavefront's 64-centroid quadrant gives one block
-// minimum per query).  The grid has 8 * ceil(tiles_q / 8) * tiles_c workgroups.
-// The same tile product with asynchronous operand staging, for D a multiple of 16: stages of
-// 16 dims, operands copied global -> LDS by global_load_lds_dwordx4 (no registers, no ds_write),
-// two LDS buffers so that the copy of stage s+1 runs under the MFMA block of stage s with one
-// barrier per stage.  A direct-to-LDS load puts lane i's 16 bytes at base + 16 i, so the layout
-// is unpadded rows of four float4; bank conflicts of the operand reads are avoided by storing
-// float4 f of row r in slot f ^ ((r >> 2) & 3) (each lane simply fetches the float4 that belongs
-// to its slot).  Lane half h feeds dims [8h, 8h+8) of the stage.  buf holds 2 x (128 + 128) rows
-// x 16 floats.
-constexpr int DK = 16;                       // dims per stage
-constexpr int DBUF = 2 * GT * DK;            // floats per buffer (A rows then B rows)
-
-__device__ __forceinline__ void gemm_tile_dma(const float *__restrict__ Q, int64_t nq, int64_t q0,
-                                              const float *__restrict__ C, int64_t K, int64_t c0, int D,
-                                              float *buf, floatx16 (&acc)[2][2])
+// One 128x128 tile of <Q[q], C[j]> per workgroup of 4 wavefronts; each
+// wavefront owns a 64x64 quadrant as 2x2 v_mfma_f32_32x32x16_f16 accumulators.
+// Operands are the packed rows above, copied global -> LDS by
+// global_load_lds_dwordx4 (no registers, no ds_write) in stages of 16
+// dimensions, two LDS buffers so that the copy of stage s+1 runs under the MFMA
+// block of stage s with one barrier per stage.  A direct-to-LDS load puts lane
+// i's 16 bytes at base + 16 i, so the layout is unpadded rows of four 16-byte
+// chunks; bank conflicts of the operand reads are avoided by storing chunk f of
+// row r in slot f ^ ((r >> 2) & 3) (each lane simply fetches the chunk that
+// belongs to its slot).  Lane half h feeds dimensions [8h, 8h+8) of the stage:
+// chunks 2h (hi) and 2h+1 (lo).  All variants of the kernel use this k order,
+// so a query's distances do not depend on the batch it arrives in.
+// In acc[i][j], lane l holds query (column) wq + 32i + l%32 and element v is
+// centroid (row) wc + 32j + 8*(v/4) + 4*(l/32) + v%4, i.e. four groups of four
+// consecutive centroids, which the epilogues store as 128-bit words and reduce
+// without leaving the lane.  buf holds 2 x (128 + 128) rows x 64 bytes.
+__device__ __forceinline__ void gemm_tile(const _Float16 *__restrict__ Qp, int64_t nq, int64_t q0,
+                                          const _Float16 *__restrict__ Cp, int64_t K, int64_t c0, int Dp,
+                                          float *buf, floatx16 (&acc)[2][2])
 {
     typedef const __attribute__((address_space(1))) void *gptr_t;
     typedef __attribute__((address_space(3))) void *lptr_t;
@@ -165,13 +154,13 @@ __device__ __forceinline__ void gemm_tile_dma(const float *__restrict__ Q, int64
     for (int n = 0; n < 4; ++n) {
         const int blk = wave * 4 + n;
         const int r = (blk & 7) * 16 + (lane >> 2);                    // row inside the operand tile
-        const int f = (lane & 3) ^ ((r >> 2) & 3);                     // float4 of the row this slot holds
+        const int f = (lane & 3) ^ ((r >> 2) & 3);                     // chunk of the row this slot holds
         if (blk < 8) {
             const int64_t row = q0 + r < nq ? q0 + r : nq - 1;
-            src[n] = Q + row * D + f * 4;
+            src[n] = reinterpret_cast<const float *>(Qp) + row * Dp + f * 4;
         } else {
             const int64_t row = c0 + r < K ? c0 + r : K - 1;
-            src[n] = C + row * D + f * 4;
+            src[n] = reinterpret_cast<const float *>(Cp) + row * Dp + f * 4;
         }
     }
     auto issue = [&](int k0, float *dst) {
@@ -179,51 +168,67 @@ __device__ __forceinline__ void gemm_tile_dma(const float *__restrict__ Q, int64
         for (int n = 0; n < 4; ++n)
             __builtin_amdgcn_global_load_lds((gptr_t)(src[n] + k0), (lptr_t)(dst + (wave * 4 + n) * 256), 16, 0, 0);
     };
-    const int stages = D / DK;
+    const int stages = Dp / DK;
     issue(0, buf);
     for (int s = 0; s < stages; ++s) {
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's copies of stage s have landed
         __syncthreads();                      // ... and everyone's; all waves are done with the other buffer
         if (s + 1 < stages) issue((s + 1) * DK, buf + ((s + 1) & 1) * DBUF);
-        const float *As = buf + (s & 1) * DBUF, *Bs = As + GT * DK;
+        const float *As = buf + (s & 1) * DBUF, *Bs = As + GT * ROWF;
+        gu32x4 a[2][2], b[2][2];
 #pragma unroll
-        for (int s4 = 0; s4 < 2; ++s4) {
-            float4 a[2], b[2];
+        for (int i = 0; i < 2; ++i) {
+            const int ra = wq + i * 32 + l32, rb = wc + i * 32 + l32;
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int ra = wq + i * 32 + l32, rb = wc + i * 32 + l32;
-                a[i] = *reinterpret_cast<const float4 *>(&As[ra * DK + (((2 * h + s4) ^ ((ra >> 2) & 3)) << 2)]);
-                b[i] = *reinterpret_cast<const float4 *>(&Bs[rb * DK + (((2 * h + s4) ^ ((rb >> 2) & 3)) << 2)]);
+            for (int p = 0; p < 2; ++p) {
+                a[i][p] = *reinterpret_cast<const gu32x4 *>(&As[ra * ROWF + (((2 * h + p) ^ ((ra >> 2) & 3)) << 2)]);
+                b[i][p] = *reinterpret_cast<const gu32x4 *>(&Bs[rb * ROWF + (((2 * h + p) ^ ((rb >> 2) & 3)) << 2)]);
             }
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const float av = e == 0 ? a[i].x : e == 1 ? a[i].y : e == 2 ? a[i].z : a[i].w;
-                        const float bv = e == 0 ? b[j].x : e == 1 ? b[j].y : e == 2 ? b[j].z : b[j].w;
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av, acc[i][j], 0, 0, 0);
-                    }
         }
+        // the four accumulators are independent: cycle through them so that no MFMA
+        // waits for the one issued just before it
+#pragma unroll
+        for (int e = 0; e < 3; ++e)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = mfma3(b[j], a[i], acc[i][j], e);
     }
     __syncthreads();   // operands are dead: the buffers may be reused
 }
 
+constexpr int BMW = 64;   // centroids per block minimum
+constexpr int N_XCD = 8;  // workgroups are dealt round-robin to the 8 XCDs, each with its own L2
+
+// Tile of workgroup b: XCD x = b % 8 owns the query tiles x, x+8, ... (a few hundred KB that
+// stay in its L2) and sweeps the centroid tiles in order, so every XCD streams the centroid
+// matrix once and the eight of them work on the same centroid tile at about the same time.
+__device__ __forceinline__ bool tile_of_block(int64_t b, int tiles_q, int64_t &q0, int64_t &c0)
+{
+    const int tq_per = (tiles_q + N_XCD - 1) / N_XCD;
+    const int xcd = (int)(b % N_XCD);
+    const int64_t local = b / N_XCD;
+    const int tq = (int)(local % tq_per) * N_XCD + xcd;
+    q0 = (int64_t)tq * GT;
+    c0 = (local / tq_per) * GT;
+    return tq < tiles_q;
+}
+
 constexpr int SLD = 64 + 4;   // row stride (floats) of a wavefront's 32x64 output staging area in LDS
 
-template <bool DMA>
+// Dt[q][j] = max(0, qn[q] + cn[j] - 2 <Q[q], C[j]>), and bm[q][b] = the minimum
+// of Dt[q][64b .. 64b+63] (each wavefront's 64-centroid quadrant gives one block
+// minimum per query).  qsi[q] and csi[0] are the inverse operand scales.  The
+// grid has 8 * ceil(tiles_q / 8) * tiles_c workgroups.
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void coarse_gemm_kernel(
-    const float *__restrict__ Q, const float *__restrict__ qn, int64_t nq,
-    const float *__restrict__ C, const float *__restrict__ cn, int64_t K, int D,
-    float *__restrict__ Dt, float *__restrict__ bm, int nb, int tiles_q)
+    const _Float16 *__restrict__ Qp, const float *__restrict__ qn, const float *__restrict__ qsi, int64_t nq,
+    const _Float16 *__restrict__ Cp, const float *__restrict__ cn, const float *__restrict__ csi, int64_t K,
+    int Dp, float *__restrict__ Dt, float *__restrict__ bm, int nb, int tiles_q)
 {
-    // operands (register-staged: two padded 128x32 tiles; DMA: two buffers of 256x16), reused as output staging
-    __shared__ __attribute__((aligned(16))) float ops[DMA ? 4 * 32 * SLD : 2 * GT * GLD];
-    static_assert(2 * DBUF <= 4 * 32 * SLD, "the DMA buffers must fit the staging area");
+    // two operand buffers of 256 rows x 64 bytes, reused as output staging
+    __shared__ __attribute__((aligned(16))) float ops[4 * 32 * SLD];
+    static_assert(2 * DBUF <= 4 * 32 * SLD, "the operand buffers must fit the staging area");
     __shared__ __attribute__((aligned(16))) float cns[GT];
-    static_assert(4 * 32 * SLD <= 2 * GT * GLD, "the four staging areas must fit the operand buffers");
-    float *As = ops, *Bs = ops + GT * GLD;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     int64_t q0, c0;
     if (!tile_of_block(blockIdx.x, tiles_q, q0, c0)) return;
@@ -231,9 +236,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     const int l32 = lane & 31, h = lane >> 5;
     if (threadIdx.x < GT) cns[threadIdx.x] = c0 + threadIdx.x < K ? cn[c0 + threadIdx.x] : 0.f;
     floatx16 acc[2][2];
-    // both end with a barrier: cns is visible, operands are dead
-    if (DMA) gemm_tile_dma(Q, nq, q0, C, K, c0, D, ops, acc);
-    else gemm_tile(Q, nq, q0, C, K, c0, D, As, Bs, acc);
+    gemm_tile(Qp, nq, q0, Cp, K, c0, Dp, ops, acc);   // ends with a barrier: cns is visible, operands are dead
+    const float m2c = -2.f * csi[0];
     const bool vec = (K & 3) == 0;
     const int64_t blk = (c0 + wc) / BMW;
     float *stage = ops + wave * (32 * SLD);
@@ -242,6 +246,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     for (int i = 0; i < 2; ++i) {
         const int64_t q = q0 + wq + i * 32 + l32;
         const float qr = q < nq ? qn[q] : 0.f;
+        const float m2 = q < nq ? m2c * qsi[q] : 0.f;
         float m = INFINITY;
         // distances of 32 queries x 64 centroids into the staging area, [query][centroid]
 #pragma unroll
@@ -252,10 +257,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                 const int64_t c = c0 + wc + cl;
                 const float4 cv = *reinterpret_cast<const float4 *>(&cns[wc + cl]);
                 float4 d;
-                d.x = fmaxf(fmaf(-2.f, acc[i][j][4 * g + 0], qr + cv.x), 0.f);
-                d.y = fmaxf(fmaf(-2.f, acc[i][j][4 * g + 1], qr + cv.y), 0.f);
-                d.z = fmaxf(fmaf(-2.f, acc[i][j][4 * g + 2], qr + cv.z), 0.f);
-                d.w = fmaxf(fmaf(-2.f, acc[i][j][4 * g + 3], qr + cv.w), 0.f);
+                d.x = fmaxf(fmaf(m2, acc[i][j][4 * g + 0], qr + cv.x), 0.f);
+                d.y = fmaxf(fmaf(m2, acc[i][j][4 * g + 1], qr + cv.y), 0.f);
+                d.z = fmaxf(fmaf(m2, acc[i][j][4 * g + 2], qr + cv.z), 0.f);
+                d.w = fmaxf(fmaf(m2, acc[i][j][4 * g + 3], qr + cv.w), 0.f);
                 m = fminf(m, c + 0 < K ? d.x : INFINITY);
                 m = fminf(m, c + 1 < K ? d.y : INFINITY);
                 m = fminf(m, c + 2 < K ? d.z : INFINITY);
@@ -290,18 +295,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 // The same for small batches (latency mode): a workgroup takes 32 queries x 256 centroids, all
 // four wavefronts share the 32 queries and each owns 64 of the centroids (two accumulators),
 // so a batch of up to 32 queries costs a quarter of the MFMA work of the 128-query tile and
-// the kernel is bounded by streaming the centroid matrix once per 32 queries.
+// the kernel is bounded by streaming the centroid matrix once per 32 queries.  Operand rows
+// in LDS: 32 query rows then 256 centroid rows per buffer, staged like the large tile.
 constexpr int SKQ = 32, SKC = 256;
+constexpr int SKBUF = (SKQ + SKC) * ROWF;   // floats per operand buffer
 
 __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
-    const float *__restrict__ Q, const float *__restrict__ qn, int64_t nq,
-    const float *__restrict__ C, const float *__restrict__ cn, int64_t K, int D,
-    float *__restrict__ Dt, float *__restrict__ bm, int nb, int tiles_q)
+    const _Float16 *__restrict__ Qp, const float *__restrict__ qn, const float *__restrict__ qsi, int64_t nq,
+    const _Float16 *__restrict__ Cp, const float *__restrict__ cn, const float *__restrict__ csi, int64_t K,
+    int Dp, float *__restrict__ Dt, float *__restrict__ bm, int nb, int tiles_q)
 {
-    __shared__ __attribute__((aligned(16))) float ops[(SKQ + SKC) * GLD];   // operands; reused as output staging
+    typedef const __attribute__((address_space(1))) void *gptr_t;
+    typedef __attribute__((address_space(3))) void *lptr_t;
+    constexpr int OPS = 2 * SKBUF > 4 * 32 * SLD ? 2 * SKBUF : 4 * 32 * SLD;
+    __shared__ __attribute__((aligned(16))) float ops[OPS];   // operands; reused as output staging
     __shared__ __attribute__((aligned(16))) float cns[SKC];
-    static_assert(4 * 32 * SLD <= (SKQ + SKC) * GLD, "the four staging areas must fit the operand buffers");
-    float *As = ops, *Bs = ops + SKQ * GLD;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int64_t q0 = (int64_t)(blockIdx.x % tiles_q) * SKQ, c0 = (int64_t)(blockIdx.x / tiles_q) * SKC;
     const int wc = wave * 64;
@@ -312,54 +320,62 @@ __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
     for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-    float4 pa, pb[8];
-    auto fetch = [&](int k0) {
-        const int c4 = (tid & 7) * 4;
-        pa = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (k0 + c4 < D && q0 + (tid >> 3) < nq)
-            pa = *reinterpret_cast<const float4 *>(Q + (q0 + (tid >> 3)) * D + k0 + c4);
+    // 18 blocks of 16 rows per stage (2 of queries, 16 of centroids); wave w copies blocks w, w+4, ...
+    constexpr int NBLK = (SKQ + SKC) / 16, PER = (NBLK + 3) / 4;
+    const float *src[PER];
 #pragma unroll
-        for (int it = 0; it < 8; ++it) {
-            const int row = (tid >> 3) + it * 32;
-            pb[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (k0 + c4 < D && c0 + row < K)
-                pb[it] = *reinterpret_cast<const float4 *>(C + (c0 + row) * D + k0 + c4);
+    for (int n = 0; n < PER; ++n) {
+        const int blk = wave + 4 * n;
+        const int row = blk * 16 + (lane >> 2);                        // row inside the buffer
+        const bool isq = row < SKQ;
+        const int r = isq ? row : row - SKQ;                           // row inside its operand tile
+        const int f = (lane & 3) ^ ((r >> 2) & 3);
+        if (isq) {
+            const int64_t g = q0 + r < nq ? q0 + r : nq - 1;
+            src[n] = reinterpret_cast<const float *>(Qp) + g * Dp + f * 4;
+        } else {
+            const int64_t g = c0 + r < K ? c0 + r : K - 1;
+            src[n] = reinterpret_cast<const float *>(Cp) + g * Dp + f * 4;
         }
-    };
-    fetch(0);
-    for (int k0 = 0; k0 < D; k0 += GKC) {
-        const int c4 = (tid & 7) * 4;
-        *reinterpret_cast<float4 *>(&As[(tid >> 3) * GLD + c4]) = pa;
-#pragma unroll
-        for (int it = 0; it < 8; ++it)
-            *reinterpret_cast<float4 *>(&Bs[((tid >> 3) + it * 32) * GLD + c4]) = pb[it];
-        __syncthreads();
-        if (k0 + GKC < D) fetch(k0 + GKC);
-#pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) {
-            const int kc = (s4 >> 1) * 16 + h * 8 + (s4 & 1) * 4;   // same k order as the other variants
-            const float4 a = *reinterpret_cast<const float4 *>(&As[l32 * GLD + kc]);
-            float4 b[2];
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                b[j] = *reinterpret_cast<const float4 *>(&Bs[(wc + j * 32 + l32) * GLD + kc]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const float av = e == 0 ? a.x : e == 1 ? a.y : e == 2 ? a.z : a.w;
-                    const float bv = e == 0 ? b[j].x : e == 1 ? b[j].y : e == 2 ? b[j].z : b[j].w;
-                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av, acc[j], 0, 0, 0);
-                }
-        }
-        __syncthreads();
     }
+    auto issue = [&](int k0, float *dst) {
+#pragma unroll
+        for (int n = 0; n < PER; ++n)
+            if (wave + 4 * n < NBLK)
+                __builtin_amdgcn_global_load_lds((gptr_t)(src[n] + k0), (lptr_t)(dst + (wave + 4 * n) * 256), 16, 0, 0);
+    };
+    const int stages = Dp / DK;
+    issue(0, ops);
+    for (int s = 0; s < stages; ++s) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (s + 1 < stages) issue((s + 1) * DK, ops + ((s + 1) & 1) * SKBUF);
+        const float *As = ops + (s & 1) * SKBUF, *Bs = As + SKQ * ROWF;
+        gu32x4 a[2], b[2][2];
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+            a[p] = *reinterpret_cast<const gu32x4 *>(&As[l32 * ROWF + (((2 * h + p) ^ ((l32 >> 2) & 3)) << 2)]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int rb = wc + j * 32 + l32;
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+                b[j][p] = *reinterpret_cast<const gu32x4 *>(&Bs[rb * ROWF + (((2 * h + p) ^ ((rb >> 2) & 3)) << 2)]);
+        }
+#pragma unroll
+        for (int e = 0; e < 3; ++e)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[j] = mfma3(b[j], a, acc[j], e);
+    }
+    __syncthreads();
+    const float m2c = -2.f * csi[0];
     const bool vec = (K & 3) == 0;
     const int64_t blk = (c0 + wc) / BMW;
     float *stage = ops + wave * (32 * SLD);
     const int sr = lane >> 4, sc = (lane & 15) * 4;
     const int64_t q = q0 + l32;
     const float qr = q < nq ? qn[q] : 0.f;
+    const float m2 = q < nq ? m2c * qsi[q] : 0.f;
     float m = INFINITY;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
@@ -369,10 +385,10 @@ __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
             const int64_t c = c0 + wc + cl;
             const float4 cv = *reinterpret_cast<const float4 *>(&cns[wc + cl]);
             float4 d;
-            d.x = fmaxf(fmaf(-2.f, acc[j][4 * g + 0], qr + cv.x), 0.f);
-            d.y = fmaxf(fmaf(-2.f, acc[j][4 * g + 1], qr + cv.y), 0.f);
-            d.z = fmaxf(fmaf(-2.f, acc[j][4 * g + 2], qr + cv.z), 0.f);
-            d.w = fmaxf(fmaf(-2.f, acc[j][4 * g + 3], qr + cv.w), 0.f);
+            d.x = fmaxf(fmaf(m2, acc[j][4 * g + 0], qr + cv.x), 0.f);
+            d.y = fmaxf(fmaf(m2, acc[j][4 * g + 1], qr + cv.y), 0.f);
+            d.z = fmaxf(fmaf(m2, acc[j][4 * g + 2], qr + cv.z), 0.f);
+            d.w = fmaxf(fmaf(m2, acc[j][4 * g + 3], qr + cv.w), 0.f);
             m = fminf(m, c + 0 < K ? d.x : INFINITY);
             m = fminf(m, c + 1 < K ? d.y : INFINITY);
             m = fminf(m, c + 2 < K ? d.z : INFINITY);
@@ -406,12 +422,11 @@ __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
 // tiles with a 64-bit atomic minimum; no distance tile is written.  best[]
 // must be pre-filled with all ones.
 __global__ __launch_bounds__(256) void coarse_argmin_kernel(
-    const float *__restrict__ Q, const float *__restrict__ qn, int64_t nq,
-    const float *__restrict__ C, const float *__restrict__ cn, int64_t K, int D,
-    unsigned long long *__restrict__ best, int tiles_q)
+    const _Float16 *__restrict__ Qp, const float *__restrict__ qn, const float *__restrict__ qsi, int64_t nq,
+    const _Float16 *__restrict__ Cp, const float *__restrict__ cn, const float *__restrict__ csi, int64_t K,
+    int Dp, unsigned long long *__restrict__ best, int tiles_q)
 {
-    __shared__ __attribute__((aligned(16))) float As[GT * GLD];
-    __shared__ __attribute__((aligned(16))) float Bs[GT * GLD];
+    __shared__ __attribute__((aligned(16))) float ops[2 * DBUF];
     __shared__ __attribute__((aligned(16))) float cns[GT];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     int64_t q0, c0;
@@ -420,11 +435,13 @@ __global__ __launch_bounds__(256) void coarse_argmin_kernel(
     const int l32 = lane & 31, h = lane >> 5;
     if (threadIdx.x < GT) cns[threadIdx.x] = c0 + threadIdx.x < K ? cn[c0 + threadIdx.x] : 0.f;
     floatx16 acc[2][2];
-    gemm_tile(Q, nq, q0, C, K, c0, D, As, Bs, acc);
+    gemm_tile(Qp, nq, q0, Cp, K, c0, Dp, ops, acc);
+    const float m2c = -2.f * csi[0];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int64_t q = q0 + wq + i * 32 + l32;
         const float qr = q < nq ? qn[q] : 0.f;
+        const float m2 = q < nq ? m2c * qsi[q] : 0.f;
         unsigned long long key = ~0ull;
 #pragma unroll
         for (int j = 0; j < 2; ++j)
@@ -433,7 +450,7 @@ __global__ __launch_bounds__(256) void coarse_argmin_kernel(
                 const int cl = wc + j * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
                 const int64_t c = c0 + cl;
                 if (c < K) {
-                    float d = fmaxf(fmaf(-2.f, acc[i][j][v], qr + cns[cl]), 0.f);
+                    float d = fmaxf(fmaf(m2, acc[i][j][v], qr + cns[cl]), 0.f);
                     unsigned long long kc = ((unsigned long long)float_key(d) << 32) | (uint32_t)c;
                     key = kc < key ? kc : key;
                 }

@@ -94,14 +94,34 @@ int check_trained(const ivf_index_desc *d)
 }
 
 // ------------------------------------------------------------ stage 1 driver
-int launch_coarse(const float *x, const float *xn, int64_t nq, const float *C, const float *cn,
-                  int64_t K, int D, float *Dt, float *bm, hipStream_t st)
+// Packs the rows of X for the GEMM (hi/lo fp16 stages, see split_rows_kernel) and writes their
+// squared norms and inverse scales.  gmax != NULL: one scale for the whole matrix (gmax is a
+// device word used for the reduction, inv receives one float); else one scale per row.
+int pack_rows(const float *X, int64_t n, int D, uint32_t *gmax, _Float16 *P, float *norm, float *inv,
+              hipStream_t st)
+{
+    if (n <= 0) return IVF_OK;
+    if (gmax) {
+        HIPCHK(hipMemsetAsync(gmax, 0, sizeof(uint32_t), st));
+        const int64_t count = n * D;
+        int64_t grid = (count + 255) / 256;
+        if (grid > 16384) grid = 16384;
+        absmax_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(X, count, gmax);
+        LAUNCHCHK("absmax_kernel");
+    }
+    split_rows_kernel<<<dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st>>>(X, n, D, gmax, P, norm, inv);
+    LAUNCHCHK("split_rows_kernel");
+    return IVF_OK;
+}
+
+int launch_coarse(const _Float16 *xp, const float *xn, const float *xsi, int64_t nq, const _Float16 *Cp,
+                  const float *cn, const float *csi, int64_t K, int Dp, float *Dt, float *bm, hipStream_t st)
 {
     const int nb = (int)((K + BMW - 1) / BMW);
     if (nq <= 2 * SKQ) {   // small batch: 32-query tiles
         int tiles_q = (int)((nq + SKQ - 1) / SKQ);
         int64_t grid = tiles_q * ((K + SKC - 1) / SKC);
-        coarse_gemm_skinny_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(x, xn, nq, C, cn, K, D, Dt, bm, nb, tiles_q);
+        coarse_gemm_skinny_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xp, xn, xsi, nq, Cp, cn, csi, K, Dp, Dt, bm, nb, tiles_q);
         LAUNCHCHK("coarse_gemm_skinny_kernel");
         return IVF_OK;
     }
@@ -109,10 +129,7 @@ int launch_coarse(const float *x, const float *xn, int64_t nq, const float *C, c
     int64_t tiles_c = (K + GT - 1) / GT;
     int64_t grid = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * tiles_c;
     if (grid >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
-    if (D % DK == 0)
-        coarse_gemm_kernel<true><<<dim3((unsigned)grid), dim3(256), 0, st>>>(x, xn, nq, C, cn, K, D, Dt, bm, nb, tiles_q);
-    else
-        coarse_gemm_kernel<false><<<dim3((unsigned)grid), dim3(256), 0, st>>>(x, xn, nq, C, cn, K, D, Dt, bm, nb, tiles_q);
+    coarse_gemm_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xp, xn, xsi, nq, Cp, cn, csi, K, Dp, Dt, bm, nb, tiles_q);
     LAUNCHCHK("coarse_gemm_kernel");
     return IVF_OK;
 }
@@ -136,12 +153,14 @@ struct ivf_index {
     int D = 0, M = 0, L = 0;
     int64_t K = 0, N = 0;
     float *centroids = nullptr, *cnorm = nullptr, *alpha = nullptr, *cst = nullptr;
+    _Float16 *cpk = nullptr;     // centroids packed for the GEMM
+    float *csi = nullptr;        // csi[0] inverse scale of the packed centroids; csi[1] reduction word
     float *codebook = nullptr, *const_table = nullptr;
     int32_t *nbr = nullptr, *ids = nullptr;
     uint4 *sub_info = nullptr;   // per subregion: block offset, first position, length
     uint8_t *blocks = nullptr;
     int64_t scratch_limit = 8ll << 30;
-    Buf dt, bm, qn, probe_id, probe_d, desc, lut, partial;
+    Buf dt, bm, qn, qpk, qsi, probe_id, probe_d, desc, lut, partial;
     // optional per-stage timing with HIP events on the caller's stream
     bool profile = false;
     std::vector<hipEvent_t> ev[IVF_N_STAGES + 1];   // ev[s][i], ev[s+1][i] bracket stage s of pass i
@@ -165,6 +184,7 @@ extern "C" void ivf_free_index(ivf_index *ix)
     (void)hipDeviceSynchronize();
     void *owned[] = {ix->centroids, ix->cnorm, ix->alpha, ix->cst, ix->codebook, ix->const_table,
                      ix->nbr, ix->ids, ix->sub_info, ix->blocks, ix->dt.p, ix->bm.p, ix->qn.p,
+                     ix->cpk, ix->csi, ix->qpk.p, ix->qsi.p,
                      ix->probe_id.p, ix->probe_d.p, ix->desc.p, ix->lut.p, ix->partial.p};
     for (void *p : owned)
         if (p) (void)hipFree(p);
@@ -204,8 +224,10 @@ int load_impl(const ivf_index_desc *d, hipStream_t st, ivf_index *ix)
     if ((rc = dev_copy(ix->ids, d->ids, (size_t)N, st))) return rc;
 
     HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->cnorm), (size_t)K * sizeof(float)));
-    row_norm_kernel<<<dim3((unsigned)((K + 3) / 4)), dim3(256), 0, st>>>(ix->centroids, K, D, ix->cnorm);
-    LAUNCHCHK("row_norm_kernel");
+    HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->cpk), (size_t)K * packed_dim(D) * 2 * sizeof(_Float16)));
+    HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->csi), 2 * sizeof(float)));
+    if ((rc = pack_rows(ix->centroids, K, D, reinterpret_cast<uint32_t *>(ix->csi + 1), ix->cpk, ix->cnorm, ix->csi, st)))
+        return rc;
     HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->cst), (size_t)nsub * sizeof(float)));
     cst_kernel<<<dim3((unsigned)((nsub + 255) / 256)), dim3(256), 0, st>>>(ix->alpha, d->cs_dist2, L, nsub, ix->cst);
     LAUNCHCHK("cst_kernel");
@@ -311,6 +333,9 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
     const int64_t nb = (K + BMW - 1) / BMW;
     if ((rc = ensure(ix->bm, (size_t)tile * nb * sizeof(float)))) return rc;
     if ((rc = ensure(ix->qn, (size_t)tile * sizeof(float)))) return rc;
+    const int Dp = packed_dim(D);
+    if ((rc = ensure(ix->qpk, (size_t)tile * Dp * 2 * sizeof(_Float16)))) return rc;
+    if ((rc = ensure(ix->qsi, (size_t)tile * sizeof(float)))) return rc;
     if ((rc = ensure(ix->probe_id, (size_t)tile * P * sizeof(int32_t)))) return rc;
     if ((rc = ensure(ix->probe_d, (size_t)tile * P * sizeof(float)))) return rc;
     if ((rc = ensure(ix->desc, (size_t)tile * S * sizeof(SubDesc)))) return rc;
@@ -353,9 +378,10 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
             return IVF_OK;
         };
         if ((rc = mark(0))) return rc;
-        row_norm_kernel<<<dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st>>>(Q, n, D, qn);
-        LAUNCHCHK("row_norm_kernel");
-        if ((rc = launch_coarse(Q, qn, n, ix->centroids, ix->cnorm, K, D, Dt, bm, st))) return rc;
+        _Float16 *qpk = static_cast<_Float16 *>(ix->qpk.p);
+        float *qsi = static_cast<float *>(ix->qsi.p);
+        if ((rc = pack_rows(Q, n, D, nullptr, qpk, qn, qsi, st))) return rc;
+        if ((rc = launch_coarse(qpk, qn, qsi, n, ix->cpk, ix->cnorm, ix->csi, K, Dp, Dt, bm, st))) return rc;
         if ((rc = mark(1))) return rc;
         if ((rc = launch_probe_select(Dt, bm, n, K, P, pid, pd, st))) return rc;
         if ((rc = mark(2))) return rc;
@@ -444,28 +470,34 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
     if (tile < 1) tile = 1;
     if (tile >= nq) tile = nq;
     else if (tile >= GT) tile -= tile % GT;
-    float *cn = nullptr, *xn = nullptr, *Dt = nullptr, *bm = nullptr;
+    float *cn = nullptr, *xn = nullptr, *Dt = nullptr, *bm = nullptr, *csi = nullptr, *xsi = nullptr;
+    _Float16 *cpk = nullptr, *xpk = nullptr;
     const int64_t nb = (K + BMW - 1) / BMW;
+    const int Dp = packed_dim(D);
     int rc = IVF_OK;
     auto body = [&]() -> int {
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&cn), (size_t)K * sizeof(float)));
-        row_norm_kernel<<<dim3((unsigned)((K + 3) / 4)), dim3(256), 0, st>>>(centroids, K, D, cn);
-        LAUNCHCHK("row_norm_kernel");
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&cpk), (size_t)K * Dp * 2 * sizeof(_Float16)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&csi), 2 * sizeof(float)));
+        int r2;
+        if ((r2 = pack_rows(centroids, K, D, reinterpret_cast<uint32_t *>(csi + 1), cpk, cn, csi, st))) return r2;
         if (P == 1) {   // fused per-row minimum, no distance tile
             const int64_t chunk = 1 << 20;
+            const int64_t cn_rows = nq < chunk ? nq : chunk;
             unsigned long long *best = nullptr;
-            HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), (size_t)(nq < chunk ? nq : chunk) * sizeof(float)));
-            HIPCHK(hipMalloc(reinterpret_cast<void **>(&Dt), (size_t)(nq < chunk ? nq : chunk) * sizeof(unsigned long long)));
+            HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), (size_t)cn_rows * sizeof(float)));
+            HIPCHK(hipMalloc(reinterpret_cast<void **>(&xsi), (size_t)cn_rows * sizeof(float)));
+            HIPCHK(hipMalloc(reinterpret_cast<void **>(&xpk), (size_t)cn_rows * Dp * 2 * sizeof(_Float16)));
+            HIPCHK(hipMalloc(reinterpret_cast<void **>(&Dt), (size_t)cn_rows * sizeof(unsigned long long)));
             best = reinterpret_cast<unsigned long long *>(Dt);
             for (int64_t q0 = 0; q0 < nq; q0 += chunk) {
                 const int64_t n = (nq - q0 < chunk) ? nq - q0 : chunk;
                 HIPCHK(hipMemsetAsync(best, 0xFF, (size_t)n * sizeof(unsigned long long), st));
-                row_norm_kernel<<<dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st>>>(x + q0 * D, n, D, xn);
-                LAUNCHCHK("row_norm_kernel");
+                if ((r2 = pack_rows(x + q0 * D, n, D, nullptr, xpk, xn, xsi, st))) return r2;
                 int tiles_q = (int)((n + GT - 1) / GT);
                 int64_t grid = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * ((K + GT - 1) / GT);
                 if (grid >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
-                coarse_argmin_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(x + q0 * D, xn, n, centroids, cn, K, D, best, tiles_q);
+                coarse_argmin_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xpk, xn, xsi, n, cpk, cn, csi, K, Dp, best, tiles_q);
                 LAUNCHCHK("coarse_argmin_kernel");
                 argmin_unpack_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(best, n, out_id + q0, out_d + q0);
                 LAUNCHCHK("argmin_unpack_kernel");
@@ -474,14 +506,14 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
             return IVF_OK;
         }
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), (size_t)tile * sizeof(float)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xsi), (size_t)tile * sizeof(float)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xpk), (size_t)tile * Dp * 2 * sizeof(_Float16)));
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&Dt), (size_t)tile * K * sizeof(float)));
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&bm), (size_t)tile * nb * sizeof(float)));
         for (int64_t q0 = 0; q0 < nq; q0 += tile) {
             const int64_t n = (nq - q0 < tile) ? nq - q0 : tile;
-            row_norm_kernel<<<dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st>>>(x + q0 * D, n, D, xn);
-            LAUNCHCHK("row_norm_kernel");
-            int r2;
-            if ((r2 = launch_coarse(x + q0 * D, xn, n, centroids, cn, K, D, Dt, bm, st))) return r2;
+            if ((r2 = pack_rows(x + q0 * D, n, D, nullptr, xpk, xn, xsi, st))) return r2;
+            if ((r2 = launch_coarse(xpk, xn, xsi, n, cpk, cn, csi, K, Dp, Dt, bm, st))) return r2;
             if ((r2 = launch_probe_select(Dt, bm, n, K, P, out_id + q0 * P, out_d + q0 * P, st))) return r2;
         }
         HIPCHK(hipStreamSynchronize(st));
@@ -492,6 +524,10 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
     (void)hipStreamSynchronize(st);
     if (cn) (void)hipFree(cn);
     if (xn) (void)hipFree(xn);
+    if (csi) (void)hipFree(csi);
+    if (xsi) (void)hipFree(xsi);
+    if (cpk) (void)hipFree(cpk);
+    if (xpk) (void)hipFree(xpk);
     if (Dt) (void)hipFree(Dt);
     if (bm) (void)hipFree(bm);
     g_err = keep;

@@ -164,7 +164,10 @@ struct ChunkRegs {
 };
 
 // Find the owner of every record of the chunk starting at flattened index t0
-// and issue its two loads.
+// and issue its two loads.  Every lane issues both loads of every step whatever
+// T is (lanes without a record read the address held in slot 0 of the stage),
+// so the number of loads in flight is the same on every path and a chunk can
+// be waited for while the one issued after it is still outstanding.
 template <int M>
 __device__ __forceinline__ void scan_issue(ChunkRegs<M> &r, WaveStage &st, uint32_t t0, uint32_t T,
                                            uint32_t len, uint32_t pre, uint32_t &carry)
@@ -193,19 +196,17 @@ __device__ __forceinline__ void scan_issue(ChunkRegs<M> &r, WaveStage &st, uint3
         bool act = t < T && o > 0;
         const uint32_t oi = act ? (o - 1) & (WAVE - 1) : 0;   // always inside the stage
         const uint4 db = st.b[oi];
-        const uint32_t c = t - db.x;
+        const uint4 da = st.a[oi];
+        uint32_t c = t - db.x;
         act = act && c < db.y;                     // never read outside the owner's block
+        c = act ? c : 0u;
         r.c[u] = act ? db.w + c : 0xFFFFFFFFu;
         r.base[u] = __uint_as_float(db.z);
-        r.cb[u] = 0;
-        if (act) {
-            const uint4 da = st.a[oi];
-            typedef const __attribute__((address_space(1))) code_t *gcode_p;   // global, not flat, loads
-            typedef const __attribute__((address_space(1))) uint8_t *gbyte_p;
-            const uint64_t pc = ((uint64_t)da.y << 32) | da.x, pb = ((uint64_t)da.w << 32) | da.z;
-            r.code[u] = *reinterpret_cast<gcode_p>(pc + (uint64_t)c * M);
-            r.cb[u] = *reinterpret_cast<gbyte_p>(pb + c);
-        }
+        typedef const __attribute__((address_space(1))) code_t *gcode_p;   // global, not flat, loads
+        typedef const __attribute__((address_space(1))) uint8_t *gbyte_p;
+        const uint64_t pc = ((uint64_t)da.y << 32) | da.x, pb = ((uint64_t)da.w << 32) | da.z;
+        r.code[u] = *reinterpret_cast<gcode_p>(pc + (uint64_t)c * M);
+        r.cb[u] = *reinterpret_cast<gbyte_p>(pb + c);
     }
 }
 
@@ -269,51 +270,92 @@ __global__ __launch_bounds__(SCAN_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4
     // The wavefront's descriptors form one stream of chunks that runs across batch boundaries:
     // next() stages the next batch when the current one is exhausted (the stage is only read
     // while issuing) and issues the following chunk into the given register set.
-    SubDesc sd_next;
-    sd_next.blk = 0; sd_next.pos0 = 0; sd_next.len = 0; sd_next.base = 0.f;
+    // Slot 0 of the stage always holds a readable address: the query's table until the first
+    // non-empty descriptor is staged.
+    if (lane == 0) {
+        const uint64_t dummy = reinterpret_cast<uint64_t>(lut + q * (int64_t)(M * 256));
+        st.a[0] = make_uint4((uint32_t)dummy, (uint32_t)(dummy >> 32), (uint32_t)dummy, (uint32_t)(dummy >> 32));
+        st.b[0] = make_uint4(0u, 0u, 0u, 0u);
+    }
+    wave_sync();
+    if (d_begin >= d_end) {                       // nothing kept (wave-uniform)
+        uint64_t *o = partial + ((q * nsplit + split) * SCAN_WAVES + wave) * (int64_t)k;
+        for (int i = lane; i < k; i += WAVE) o[i] = EMPTY_KEY;
+        return;
+    }
+    // Descriptor prefetch: always one load per lane (index clamped into the share), validity
+    // is applied when the batch is staged.
     int b_next = d_begin + wave * WAVE;          // first descriptor of the batch to stage next
-    if (b_next + lane < d_end) sd_next = qd[b_next + lane];
-    uint32_t len = 0, pre = 0, Tn = 0, t_next = 0, carry = 0;
-    auto next = [&](ChunkRegs<M> &r) -> bool {
-        while (t_next >= Tn) {                    // current batch exhausted (or empty): stage the next one
-            if (b_next >= d_end) return false;
-            const SubDesc sd = sd_next;
-            b_next += SCAN_WAVES * WAVE;
-            sd_next.blk = 0; sd_next.pos0 = 0; sd_next.len = 0; sd_next.base = 0.f;
-            if (b_next + lane < d_end) sd_next = qd[b_next + lane];   // prefetch the batch after
-            len = sd.len;
-            const uint32_t inc = wave_inclusive_scan(len);
-            pre = inc - len;
-            Tn = (uint32_t)__builtin_amdgcn_readlane((int)inc, WAVE - 1);
-            t_next = 0;
-            carry = 0;
-            wave_sync();
-            const uint64_t pc = reinterpret_cast<uint64_t>(blocks) + (uint64_t)sd.blk * 64u;
-            const uint64_t pb = pc + (uint64_t)len * M;
-            const uint64_t ne = __ballot(len > 0);
-            const uint32_t slot = __builtin_amdgcn_mbcnt_hi((uint32_t)(ne >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ne, 0u));
-            if (len > 0) {
-                st.a[slot] = make_uint4((uint32_t)pc, (uint32_t)(pc >> 32), (uint32_t)pb, (uint32_t)(pb >> 32));
-                st.b[slot] = make_uint4(pre, len, __float_as_uint(sd.base), sd.pos0);
-            }
-        }
-        scan_issue<M>(r, st, t_next, Tn, len, pre, carry);
-        t_next += SCAN_CHUNK;
-        return true;
+    auto fetch_desc = [&](int b) {
+        int i = b + lane;
+        i = i < d_end ? i : d_end - 1;
+        return *reinterpret_cast<const uint4 *>(qd + i);
     };
+    uint4 sd_next = fetch_desc(b_next);
+    uint32_t len = 0, pre = 0, Tn = 0, t_next = 0, carry = 0;
+    auto stage = [&]() {
+        const uint4 sd = sd_next;                 // blk, pos0, len, base
+        const bool valid = b_next + lane < d_end;
+        b_next += SCAN_WAVES * WAVE;
+        sd_next = fetch_desc(b_next);             // prefetch the batch after (b_next may pass d_end: clamped)
+        len = valid ? sd.z : 0u;
+        const uint32_t inc = wave_inclusive_scan(len);
+        pre = inc - len;
+        Tn = (uint32_t)__builtin_amdgcn_readlane((int)inc, WAVE - 1);
+        t_next = 0;
+        carry = 0;
+        wave_sync();
+        const uint64_t pc = reinterpret_cast<uint64_t>(blocks) + (uint64_t)sd.x * 64u;
+        const uint64_t pb = pc + (uint64_t)len * M;
+        const uint64_t ne = __ballot(len > 0);
+        const uint32_t slot = __builtin_amdgcn_mbcnt_hi((uint32_t)(ne >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ne, 0u));
+        if (len > 0) {
+            st.a[slot] = make_uint4((uint32_t)pc, (uint32_t)(pc >> 32), (uint32_t)pb, (uint32_t)(pb >> 32));
+            st.b[slot] = make_uint4(pre, len, sd.w, sd.y);
+        }
+    };
+    // Issues the next chunk of the stream into r; when the stream has ended it still issues a
+    // chunk of loads with no records (so that load counts do not depend on the path taken) and
+    // returns false.
+    auto next = [&](ChunkRegs<M> &r) -> bool {
+        bool live = true;
+        while (t_next >= Tn) {                    // current batch exhausted (or empty): stage the next one
+            if (b_next >= d_end) { live = false; break; }
+            stage();
+        }
+        scan_issue<M>(r, st, t_next, live ? Tn : 0u, live ? len : 0u, pre, carry);
+        t_next += SCAN_CHUNK;
+        return live;
+    };
+    // Table lookups of the whole chunk first, as one straight run of code for all lanes (lanes
+    // without a record look up the bytes their placeholder load returned and are masked out
+    // afterwards): the 4 * (M + 1) LDS reads and the four sums are independent and overlap.
+    // Admission to the pool is rare once the threshold has tightened and is tested once per chunk.
     auto consume = [&](ChunkRegs<M> &cur) {
         theta = fminf(theta, key_float(wg_theta_key));
+        float dist[SCAN_U];
 #pragma unroll
-        for (int u = 0; u < SCAN_U; ++u) {
-            const bool active = cur.c[u] != 0xFFFFFFFFu;
-            float dist = INFINITY;
-            if (active) dist = adc_sum<M>(cur.code[u], Tb, cur.base[u] + nt[cur.cb[u]], two);
-            const bool pass = active && dist <= theta;
+        for (int u = 0; u < SCAN_U; ++u)
+            dist[u] = adc_sum<M>(cur.code[u], Tb, cur.base[u] + nt[cur.cb[u]], two);
+        bool any = false;
+#pragma unroll
+        for (int u = 0; u < SCAN_U; ++u) any = any || (cur.c[u] != 0xFFFFFFFFu && dist[u] <= theta);
+        if (__ballot(any) == 0) return;
+#pragma nounroll
+        for (int u = 0; u < SCAN_U; ++u) {        // rolled: one copy of the rarely taken path
+            float d = dist[0];
+            uint32_t c = cur.c[0];
+#pragma unroll
+            for (int j = 1; j < SCAN_U; ++j) {
+                d = u == j ? dist[j] : d;
+                c = u == j ? cur.c[j] : c;
+            }
+            const bool pass = c != 0xFFFFFFFFu && d <= theta;
             const uint64_t mask = __ballot(pass);
             if (mask) {
                 if (pass) {
                     int slot = pool_n + __popcll(mask & ((1ull << lane) - 1ull));
-                    pool[slot] = ((uint64_t)float_key(dist) << 32) | cur.c[u];
+                    pool[slot] = ((uint64_t)float_key(d) << 32) | c;
                 }
                 pool_n += __popcll(mask);
                 if (pool_n > cap - WAVE) {

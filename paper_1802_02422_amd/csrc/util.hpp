@@ -38,17 +38,6 @@ __device__ __forceinline__ void wave_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
-{
-    const int lane = threadIdx.x & (WAVE - 1);
-#pragma unroll
-    for (int o = 1; o < WAVE; o <<= 1) {
-        uint32_t t = __shfl_up(v, o, WAVE);
-        if (lane >= o) v += t;
-    }
-    return v;
-}
-
 // DPP move with 0 for lanes that have no source (shifted out of their row of 16,
 // or in a row excluded by ROW_MASK).
 template <int CTRL, int ROW_MASK>
@@ -77,6 +66,18 @@ __device__ __forceinline__ uint32_t wave_inclusive_max_scan(uint32_t v)
     t = dpp_or_zero<0x118, 0xf>(v); v = t > v ? t : v;
     t = dpp_or_zero<0x142, 0xa>(v); v = t > v ? t : v;
     t = dpp_or_zero<0x143, 0xc>(v); v = t > v ? t : v;
+    return v;
+}
+
+// Inclusive prefix sum over the 64 lanes, the same six DPP steps.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
+{
+    v += dpp_or_zero<0x111, 0xf>(v);
+    v += dpp_or_zero<0x112, 0xf>(v);
+    v += dpp_or_zero<0x114, 0xf>(v);
+    v += dpp_or_zero<0x118, 0xf>(v);
+    v += dpp_or_zero<0x142, 0xa>(v);
+    v += dpp_or_zero<0x143, 0xc>(v);
     return v;
 }
 
