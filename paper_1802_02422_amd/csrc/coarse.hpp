@@ -50,10 +50,14 @@ __global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ X
 }
 
 constexpr int DK = 16;                       // dimensions per operand stage
-__host__ __device__ inline int packed_dim(int D) { return (D + DK - 1) / DK * DK; }
+// packed width of a row: whole stages, and an even number of them (the GEMM loops are unrolled by two)
+__host__ __device__ inline int packed_dim(int D) { return (D + 2 * DK - 1) / (2 * DK) * (2 * DK); }
+// Rows a packed matrix of n rows must be allocated for: the GEMM tiles copy whole tiles of up
+// to 256 rows without clamping (rows past n are read, their products are never stored).
+__host__ __device__ inline int64_t packed_rows(int64_t n) { return (n + 255) / 256 * 256; }
 
 // Operand packing for the GEMM: row r of X ([n][D] fp32) becomes packed_dim(D)/16
-// stages of 64 bytes, stage t = [hi k0..7 | lo k0..7 | hi k8..15 | lo k8..15] of
+// (an even number of) stages of 64 bytes, stage t = [hi k0..7 | lo k0..7 | hi k8..15 | lo k8..15] of
 // dimensions 16t + k (fp16, zero beyond D), scaled by s = 2^(14 - floor(log2 m)):
 // m is the row's largest magnitude, or the whole matrix's when gmax (the result
 // of absmax_kernel) is given.  Also writes ||row||^2 and 1/s (per row, or
@@ -130,10 +134,10 @@ __device__ __forceinline__ floatx16 mfma3(const gu32x4 (&bfrag)[2], const gu32x4
 // In acc[i][j], lane l holds query (column) wq + 32i + l%32 and element v is
 // centroid (row) wc + 32j + 8*(v/4) + 4*(l/32) + v%4, i.e. four groups of four
 // consecutive centroids, which the epilogues store as 128-bit words and reduce
-// without leaving the lane.  buf holds 2 x (128 + 128) rows x 64 bytes.
+// without leaving the lane.  buf0 and buf1 each hold (128 + 128) rows x 64 bytes.
 __device__ __forceinline__ void gemm_tile(const _Float16 *__restrict__ Qp, int64_t nq, int64_t q0,
                                           const _Float16 *__restrict__ Cp, int64_t K, int64_t c0, int Dp,
-                                          float *buf, floatx16 (&acc)[2][2])
+                                          float *buf0, float *buf1, floatx16 (&acc)[2][2])
 {
     typedef const __attribute__((address_space(1))) void *gptr_t;
     typedef __attribute__((address_space(3))) void *lptr_t;
@@ -147,34 +151,23 @@ __device__ __forceinline__ void gemm_tile(const _Float16 *__restrict__ Qp, int64
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // this wave's four copy instructions per stage: blocks of 16 rows; blocks 0-7 are query rows,
-    // 8-15 centroid rows.  Rows past the end are clamped (their products are never stored).
-    const float *src[4];
-#pragma unroll
-    for (int n = 0; n < 4; ++n) {
-        const int blk = wave * 4 + n;
-        const int r = (blk & 7) * 16 + (lane >> 2);                    // row inside the operand tile
-        const int f = (lane & 3) ^ ((r >> 2) & 3);                     // chunk of the row this slot holds
-        if (blk < 8) {
-            const int64_t row = q0 + r < nq ? q0 + r : nq - 1;
-            src[n] = reinterpret_cast<const float *>(Qp) + row * Dp + f * 4;
-        } else {
-            const int64_t row = c0 + r < K ? c0 + r : K - 1;
-            src[n] = reinterpret_cast<const float *>(Cp) + row * Dp + f * 4;
-        }
-    }
+    // This wave's four copies per stage: 16-row blocks 4 wave .. 4 wave + 3 of the buffer, i.e. 64
+    // consecutive rows of one operand (waves 0-1 the query rows, 2-3 the centroid rows).  Both
+    // packed matrices are allocated up to a multiple of the tile height, so no row is clamped
+    // (products of rows past the end are never stored), and the copies are one instruction in a
+    // rolled loop: the compiler tracks only a handful of distinct LDS copies exactly.
+    const int r0 = (wave & 1) * 64 + (lane >> 2);                      // first row inside the operand tile
+    const int f = (lane & 3) ^ ((r0 >> 2) & 3);                        // chunk this slot holds (same for all four rows)
+    const float *src0 = wave < 2 ? reinterpret_cast<const float *>(Qp) + (q0 + r0) * Dp + f * 4
+                                 : reinterpret_cast<const float *>(Cp) + (c0 + r0) * Dp + f * 4;
     auto issue = [&](int k0, float *dst) {
-#pragma unroll
+#pragma nounroll
         for (int n = 0; n < 4; ++n)
-            __builtin_amdgcn_global_load_lds((gptr_t)(src[n] + k0), (lptr_t)(dst + (wave * 4 + n) * 256), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(src0 + (int64_t)n * 16 * Dp + k0),
+                                             (lptr_t)(dst + (wave * 4 + n) * 256), 16, 0, 0);
     };
-    const int stages = Dp / DK;
-    issue(0, buf);
-    for (int s = 0; s < stages; ++s) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's copies of stage s have landed
-        __syncthreads();                      // ... and everyone's; all waves are done with the other buffer
-        if (s + 1 < stages) issue((s + 1) * DK, buf + ((s + 1) & 1) * DBUF);
-        const float *As = buf + (s & 1) * DBUF, *Bs = As + GT * ROWF;
+    auto compute = [&](const float *As) {
+        const float *Bs = As + GT * ROWF;
         gu32x4 a[2][2], b[2][2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
@@ -193,6 +186,22 @@ __device__ __forceinline__ void gemm_tile(const _Float16 *__restrict__ Qp, int64
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) acc[i][j] = mfma3(b[j], a[i], acc[i][j], e);
+    };
+    // The two buffers are separate LDS objects and every step names them statically (the loop
+    // is unrolled by two): the compiler can then tell that the operand reads of one buffer do
+    // not depend on the copy in flight into the other, and leaves that copy running under the
+    // MFMA block.
+    const int stages = Dp / DK;
+    issue(0, buf0);
+    for (int s = 0; s < stages; s += 2) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's copies of stage s have landed
+        __syncthreads();                      // ... and everyone's; all waves are done with the other buffer
+        issue((s + 1) * DK, buf1);            // the number of stages is even
+        compute(buf0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (s + 2 < stages) issue((s + 2) * DK, buf0);
+        compute(buf1);
     }
     __syncthreads();   // operands are dead: the buffers may be reused
 }
@@ -216,65 +225,54 @@ __device__ __forceinline__ bool tile_of_block(int64_t b, int tiles_q, int64_t &q
 
 constexpr int SLD = 64 + 4;   // row stride (floats) of a wavefront's 32x64 output staging area in LDS
 
-// Dt[q][j] = max(0, qn[q] + cn[j] - 2 <Q[q], C[j]>), and bm[q][b] = the minimum
-// of Dt[q][64b .. 64b+63] (each wavefront's 64-centroid quadrant gives one block
-// minimum per query).  qsi[q] and csi[0] are the inverse operand scales.  The
-// grid has 8 * ceil(tiles_q / 8) * tiles_c workgroups.
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void coarse_gemm_kernel(
-    const _Float16 *__restrict__ Qp, const float *__restrict__ qn, const float *__restrict__ qsi, int64_t nq,
-    const _Float16 *__restrict__ Cp, const float *__restrict__ cn, const float *__restrict__ csi, int64_t K,
-    int Dp, float *__restrict__ Dt, float *__restrict__ bm, int nb, int tiles_q)
+// Epilogue of one 32-query x 64-centroid block held by a wavefront as two accumulators
+// (acc[j]: centroids 32j .. 32j+31 of the block): distances max(0, qr + cn + m2 * acc), the
+// block minimum per query into bm, and the distances out through the wavefront's LDS staging
+// area, [query][centroid], so that 16 lanes cover one query row and every store instruction
+// writes four rows of 256 contiguous bytes.  qb / cb: first query / centroid of the block;
+// cnw: the 64 centroid norms of the block (LDS).  EDGE = false skips all bounds checks (the
+// block lies inside Dt and K is a multiple of 4).
+template <bool EDGE>
+__device__ __forceinline__ void emit_block(const floatx16 (&acc)[2], float qr, float m2, const float *cnw,
+                                           float *stage, int64_t qb, int64_t nq, int64_t cb, int64_t K,
+                                           float *__restrict__ Dt, float *__restrict__ bm, int nb)
 {
-    // two operand buffers of 256 rows x 64 bytes, reused as output staging
-    __shared__ __attribute__((aligned(16))) float ops[4 * 32 * SLD];
-    static_assert(2 * DBUF <= 4 * 32 * SLD, "the operand buffers must fit the staging area");
-    __shared__ __attribute__((aligned(16))) float cns[GT];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    int64_t q0, c0;
-    if (!tile_of_block(blockIdx.x, tiles_q, q0, c0)) return;
-    const int wq = (wave >> 1) * 64, wc = (wave & 1) * 64;
+    const int lane = threadIdx.x & 63;
     const int l32 = lane & 31, h = lane >> 5;
-    if (threadIdx.x < GT) cns[threadIdx.x] = c0 + threadIdx.x < K ? cn[c0 + threadIdx.x] : 0.f;
-    floatx16 acc[2][2];
-    gemm_tile(Qp, nq, q0, Cp, K, c0, Dp, ops, acc);   // ends with a barrier: cns is visible, operands are dead
-    const float m2c = -2.f * csi[0];
-    const bool vec = (K & 3) == 0;
-    const int64_t blk = (c0 + wc) / BMW;
-    float *stage = ops + wave * (32 * SLD);
-    const int sr = lane >> 4, sc = (lane & 15) * 4;   // store phase: 16 lanes cover one query row of 64 centroids
+    const int sr = lane >> 4, sc = (lane & 15) * 4;
+    float m = INFINITY;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int64_t q = q0 + wq + i * 32 + l32;
-        const float qr = q < nq ? qn[q] : 0.f;
-        const float m2 = q < nq ? m2c * qsi[q] : 0.f;
-        float m = INFINITY;
-        // distances of 32 queries x 64 centroids into the staging area, [query][centroid]
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int cl = j * 32 + 8 * g + 4 * h;          // centroid of element 4g inside the quadrant
-                const int64_t c = c0 + wc + cl;
-                const float4 cv = *reinterpret_cast<const float4 *>(&cns[wc + cl]);
-                float4 d;
-                d.x = fmaxf(fmaf(m2, acc[i][j][4 * g + 0], qr + cv.x), 0.f);
-                d.y = fmaxf(fmaf(m2, acc[i][j][4 * g + 1], qr + cv.y), 0.f);
-                d.z = fmaxf(fmaf(m2, acc[i][j][4 * g + 2], qr + cv.z), 0.f);
-                d.w = fmaxf(fmaf(m2, acc[i][j][4 * g + 3], qr + cv.w), 0.f);
+        for (int g = 0; g < 4; ++g) {
+            const int cl = j * 32 + 8 * g + 4 * h;          // centroid of element 4g inside the block
+            const float4 cv = *reinterpret_cast<const float4 *>(&cnw[cl]);
+            float4 d;
+            d.x = fmaxf(fmaf(m2, acc[j][4 * g + 0], qr + cv.x), 0.f);
+            d.y = fmaxf(fmaf(m2, acc[j][4 * g + 1], qr + cv.y), 0.f);
+            d.z = fmaxf(fmaf(m2, acc[j][4 * g + 2], qr + cv.z), 0.f);
+            d.w = fmaxf(fmaf(m2, acc[j][4 * g + 3], qr + cv.w), 0.f);
+            if (EDGE) {
+                const int64_t c = cb + cl;
                 m = fminf(m, c + 0 < K ? d.x : INFINITY);
                 m = fminf(m, c + 1 < K ? d.y : INFINITY);
                 m = fminf(m, c + 2 < K ? d.z : INFINITY);
                 m = fminf(m, c + 3 < K ? d.w : INFINITY);
-                *reinterpret_cast<float4 *>(&stage[l32 * SLD + cl]) = d;
+            } else {
+                m = fminf(fminf(m, d.x), fminf(d.y, fminf(d.z, d.w)));
             }
-        m = fminf(m, __shfl_xor(m, 32, WAVE));   // the other half holds the other 32 centroids
-        if (h == 0 && q < nq && blk < nb) bm[q * nb + blk] = m;
-        wave_sync();
-        // out again with 16 lanes per query row: every store instruction writes four rows of 256 contiguous bytes
+            *reinterpret_cast<float4 *>(&stage[l32 * SLD + cl]) = d;
+        }
+    m = fminf(m, __shfl_xor(m, 32, WAVE));   // the other half holds the other 32 centroids
+    const int64_t q = qb + l32, blk = cb / BMW;
+    if (h == 0 && (!EDGE || (q < nq && blk < nb))) bm[q * nb + blk] = m;
+    wave_sync();
+    if (EDGE) {
+        const bool vec = (K & 3) == 0;
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
             const int r = it * 4 + sr;
-            const int64_t qq = q0 + wq + i * 32 + r, c = c0 + wc + sc;
+            const int64_t qq = qb + r, c = cb + sc;
             const float4 d = *reinterpret_cast<const float4 *>(&stage[r * SLD + sc]);
             if (qq < nq) {
                 float *rowp = Dt + qq * K;
@@ -288,7 +286,49 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                 }
             }
         }
-        wave_sync();
+    } else {
+        float *p = Dt + (qb + sr) * K + cb + sc;
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            *reinterpret_cast<float4 *>(p) = *reinterpret_cast<const float4 *>(&stage[(it * 4 + sr) * SLD + sc]);
+            p += 4 * K;
+        }
+    }
+    wave_sync();
+}
+
+// Dt[q][j] = max(0, qn[q] + cn[j] - 2 <Q[q], C[j]>), and bm[q][b] = the minimum
+// of Dt[q][64b .. 64b+63] (each wavefront's 64-centroid quadrant gives one block
+// minimum per query).  qsi[q] and csi[0] are the inverse operand scales.  The
+// grid has 8 * ceil(tiles_q / 8) * tiles_c workgroups.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void coarse_gemm_kernel(
+    const _Float16 *__restrict__ Qp, const float *__restrict__ qn, const float *__restrict__ qsi, int64_t nq,
+    const _Float16 *__restrict__ Cp, const float *__restrict__ cn, const float *__restrict__ csi, int64_t K,
+    int Dp, float *__restrict__ Dt, float *__restrict__ bm, int nb, int tiles_q)
+{
+    // two operand buffers of 256 rows x 64 bytes, each reused as the output staging of two wavefronts
+    __shared__ __attribute__((aligned(16))) float ops0[2 * 32 * SLD];
+    __shared__ __attribute__((aligned(16))) float ops1[2 * 32 * SLD];
+    static_assert(DBUF <= 2 * 32 * SLD, "an operand buffer must fit the staging area of two wavefronts");
+    __shared__ __attribute__((aligned(16))) float cns[GT];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int64_t q0, c0;
+    if (!tile_of_block(blockIdx.x, tiles_q, q0, c0)) return;
+    const int wq = (wave >> 1) * 64, wc = (wave & 1) * 64;
+    const int l32 = lane & 31, h = lane >> 5;
+    if (threadIdx.x < GT) cns[threadIdx.x] = c0 + threadIdx.x < K ? cn[c0 + threadIdx.x] : 0.f;
+    floatx16 acc[2][2];
+    gemm_tile(Qp, nq, q0, Cp, K, c0, Dp, ops0, ops1, acc);   // ends with a barrier: cns is visible, operands are dead
+    const float m2c = -2.f * csi[0];
+    float *stage = (wave < 2 ? ops0 : ops1) + (wave & 1) * (32 * SLD);
+    const bool interior = q0 + GT <= nq && c0 + GT <= K && (K & 3) == 0;   // uniform over the workgroup
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int64_t qb = q0 + wq + i * 32, q = qb + l32;
+        const float qr = q < nq ? qn[q] : 0.f;
+        const float m2 = q < nq ? m2c * qsi[q] : 0.f;
+        if (interior) emit_block<false>(acc[i], qr, m2, cns + wc, stage, qb, nq, c0 + wc, K, Dt, bm, nb);
+        else emit_block<true>(acc[i], qr, m2, cns + wc, stage, qb, nq, c0 + wc, K, Dt, bm, nb);
     }
 }
 
@@ -307,8 +347,10 @@ __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
 {
     typedef const __attribute__((address_space(1))) void *gptr_t;
     typedef __attribute__((address_space(3))) void *lptr_t;
-    constexpr int OPS = 2 * SKBUF > 4 * 32 * SLD ? 2 * SKBUF : 4 * 32 * SLD;
-    __shared__ __attribute__((aligned(16))) float ops[OPS];   // operands; reused as output staging
+    // two operand buffers, each reused as the output staging of two wavefronts
+    constexpr int OPS = SKBUF > 2 * 32 * SLD ? SKBUF : 2 * 32 * SLD;
+    __shared__ __attribute__((aligned(16))) float ops0[OPS];
+    __shared__ __attribute__((aligned(16))) float ops1[OPS];
     __shared__ __attribute__((aligned(16))) float cns[SKC];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int64_t q0 = (int64_t)(blockIdx.x % tiles_q) * SKQ, c0 = (int64_t)(blockIdx.x / tiles_q) * SKC;
@@ -320,37 +362,22 @@ __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
     for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-    // 18 blocks of 16 rows per stage (2 of queries, 16 of centroids); wave w copies blocks w, w+4, ...
-    constexpr int NBLK = (SKQ + SKC) / 16, PER = (NBLK + 3) / 4;
-    const float *src[PER];
-#pragma unroll
-    for (int n = 0; n < PER; ++n) {
-        const int blk = wave + 4 * n;
-        const int row = blk * 16 + (lane >> 2);                        // row inside the buffer
-        const bool isq = row < SKQ;
-        const int r = isq ? row : row - SKQ;                           // row inside its operand tile
-        const int f = (lane & 3) ^ ((r >> 2) & 3);
-        if (isq) {
-            const int64_t g = q0 + r < nq ? q0 + r : nq - 1;
-            src[n] = reinterpret_cast<const float *>(Qp) + g * Dp + f * 4;
-        } else {
-            const int64_t g = c0 + r < K ? c0 + r : K - 1;
-            src[n] = reinterpret_cast<const float *>(Cp) + g * Dp + f * 4;
-        }
-    }
+    // Copies per stage: wave w takes the centroid blocks (16 rows each) w, w+4, w+8, w+12 with one
+    // instruction in a rolled loop, waves 0 and 1 also one block of query rows (see gemm_tile).
+    const int rl = lane >> 2;
+    const int fq = (lane & 3) ^ ((rl >> 2) & 3);                       // (r >> 2) & 3 depends on the row inside the block only
+    const float *srcc = reinterpret_cast<const float *>(Cp) + (c0 + wave * 16 + rl) * Dp + fq * 4;
+    const float *srcq = reinterpret_cast<const float *>(Qp) + (q0 + (wave & 1) * 16 + rl) * Dp + fq * 4;
     auto issue = [&](int k0, float *dst) {
-#pragma unroll
-        for (int n = 0; n < PER; ++n)
-            if (wave + 4 * n < NBLK)
-                __builtin_amdgcn_global_load_lds((gptr_t)(src[n] + k0), (lptr_t)(dst + (wave + 4 * n) * 256), 16, 0, 0);
+#pragma nounroll
+        for (int n = 0; n < 4; ++n)
+            __builtin_amdgcn_global_load_lds((gptr_t)(srcc + (int64_t)n * 64 * Dp + k0),
+                                             (lptr_t)(dst + (2 + wave + 4 * n) * 256), 16, 0, 0);
+        if (wave < 2)
+            __builtin_amdgcn_global_load_lds((gptr_t)(srcq + k0), (lptr_t)(dst + wave * 256), 16, 0, 0);
     };
-    const int stages = Dp / DK;
-    issue(0, ops);
-    for (int s = 0; s < stages; ++s) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
-        if (s + 1 < stages) issue((s + 1) * DK, ops + ((s + 1) & 1) * SKBUF);
-        const float *As = ops + (s & 1) * SKBUF, *Bs = As + SKQ * ROWF;
+    auto compute = [&](const float *As) {
+        const float *Bs = As + SKQ * ROWF;
         gu32x4 a[2], b[2][2];
 #pragma unroll
         for (int p = 0; p < 2; ++p)
@@ -366,55 +393,28 @@ __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
         for (int e = 0; e < 3; ++e)
 #pragma unroll
             for (int j = 0; j < 2; ++j) acc[j] = mfma3(b[j], a, acc[j], e);
+    };
+    const int stages = Dp / DK;
+    issue(0, ops0);
+    for (int s = 0; s < stages; s += 2) {     // unrolled by two, see gemm_tile
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        issue((s + 1) * DK, ops1);
+        compute(ops0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (s + 2 < stages) issue((s + 2) * DK, ops0);
+        compute(ops1);
     }
     __syncthreads();
     const float m2c = -2.f * csi[0];
-    const bool vec = (K & 3) == 0;
-    const int64_t blk = (c0 + wc) / BMW;
-    float *stage = ops + wave * (32 * SLD);
-    const int sr = lane >> 4, sc = (lane & 15) * 4;
+    float *stage = (wave < 2 ? ops0 : ops1) + (wave & 1) * (32 * SLD);
     const int64_t q = q0 + l32;
     const float qr = q < nq ? qn[q] : 0.f;
     const float m2 = q < nq ? m2c * qsi[q] : 0.f;
-    float m = INFINITY;
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int cl = j * 32 + 8 * g + 4 * h;
-            const int64_t c = c0 + wc + cl;
-            const float4 cv = *reinterpret_cast<const float4 *>(&cns[wc + cl]);
-            float4 d;
-            d.x = fmaxf(fmaf(m2, acc[j][4 * g + 0], qr + cv.x), 0.f);
-            d.y = fmaxf(fmaf(m2, acc[j][4 * g + 1], qr + cv.y), 0.f);
-            d.z = fmaxf(fmaf(m2, acc[j][4 * g + 2], qr + cv.z), 0.f);
-            d.w = fmaxf(fmaf(m2, acc[j][4 * g + 3], qr + cv.w), 0.f);
-            m = fminf(m, c + 0 < K ? d.x : INFINITY);
-            m = fminf(m, c + 1 < K ? d.y : INFINITY);
-            m = fminf(m, c + 2 < K ? d.z : INFINITY);
-            m = fminf(m, c + 3 < K ? d.w : INFINITY);
-            *reinterpret_cast<float4 *>(&stage[l32 * SLD + cl]) = d;
-        }
-    m = fminf(m, __shfl_xor(m, 32, WAVE));
-    if (h == 0 && q < nq && blk < nb) bm[q * nb + blk] = m;
-    wave_sync();
-#pragma unroll
-    for (int it = 0; it < 8; ++it) {
-        const int r = it * 4 + sr;
-        const int64_t qq = q0 + r, c = c0 + wc + sc;
-        const float4 d = *reinterpret_cast<const float4 *>(&stage[r * SLD + sc]);
-        if (qq < nq) {
-            float *rowp = Dt + qq * K;
-            if (vec && c + 3 < K) {
-                *reinterpret_cast<float4 *>(rowp + c) = d;
-            } else {
-                const float dv[4] = {d.x, d.y, d.z, d.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (c + e < K) rowp[c + e] = dv[e];
-            }
-        }
-    }
+    const bool interior = q0 + SKQ <= nq && c0 + SKC <= K && (K & 3) == 0;
+    if (interior) emit_block<false>(acc, qr, m2, cns + wc, stage, q0, nq, c0 + wc, K, Dt, bm, nb);
+    else emit_block<true>(acc, qr, m2, cns + wc, stage, q0, nq, c0 + wc, K, Dt, bm, nb);
 }
 
 // Nearest centroid only (P = 1): the same tile product, reduced on the fly to
@@ -426,7 +426,8 @@ __global__ __launch_bounds__(256) void coarse_argmin_kernel(
     const _Float16 *__restrict__ Cp, const float *__restrict__ cn, const float *__restrict__ csi, int64_t K,
     int Dp, unsigned long long *__restrict__ best, int tiles_q)
 {
-    __shared__ __attribute__((aligned(16))) float ops[2 * DBUF];
+    __shared__ __attribute__((aligned(16))) float ops0[DBUF];
+    __shared__ __attribute__((aligned(16))) float ops1[DBUF];
     __shared__ __attribute__((aligned(16))) float cns[GT];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     int64_t q0, c0;
@@ -435,7 +436,7 @@ __global__ __launch_bounds__(256) void coarse_argmin_kernel(
     const int l32 = lane & 31, h = lane >> 5;
     if (threadIdx.x < GT) cns[threadIdx.x] = c0 + threadIdx.x < K ? cn[c0 + threadIdx.x] : 0.f;
     floatx16 acc[2][2];
-    gemm_tile(Qp, nq, q0, Cp, K, c0, Dp, ops, acc);
+    gemm_tile(Qp, nq, q0, Cp, K, c0, Dp, ops0, ops1, acc);
     const float m2c = -2.f * csi[0];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {

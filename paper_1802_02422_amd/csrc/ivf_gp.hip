@@ -224,7 +224,7 @@ int load_impl(const ivf_index_desc *d, hipStream_t st, ivf_index *ix)
     if ((rc = dev_copy(ix->ids, d->ids, (size_t)N, st))) return rc;
 
     HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->cnorm), (size_t)K * sizeof(float)));
-    HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->cpk), (size_t)K * packed_dim(D) * 2 * sizeof(_Float16)));
+    HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->cpk), (size_t)packed_rows(K) * packed_dim(D) * 2 * sizeof(_Float16)));
     HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->csi), 2 * sizeof(float)));
     if ((rc = pack_rows(ix->centroids, K, D, reinterpret_cast<uint32_t *>(ix->csi + 1), ix->cpk, ix->cnorm, ix->csi, st)))
         return rc;
@@ -334,7 +334,7 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
     if ((rc = ensure(ix->bm, (size_t)tile * nb * sizeof(float)))) return rc;
     if ((rc = ensure(ix->qn, (size_t)tile * sizeof(float)))) return rc;
     const int Dp = packed_dim(D);
-    if ((rc = ensure(ix->qpk, (size_t)tile * Dp * 2 * sizeof(_Float16)))) return rc;
+    if ((rc = ensure(ix->qpk, (size_t)packed_rows(tile) * Dp * 2 * sizeof(_Float16)))) return rc;
     if ((rc = ensure(ix->qsi, (size_t)tile * sizeof(float)))) return rc;
     if ((rc = ensure(ix->probe_id, (size_t)tile * P * sizeof(int32_t)))) return rc;
     if ((rc = ensure(ix->probe_d, (size_t)tile * P * sizeof(float)))) return rc;
@@ -477,7 +477,7 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
     int rc = IVF_OK;
     auto body = [&]() -> int {
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&cn), (size_t)K * sizeof(float)));
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&cpk), (size_t)K * Dp * 2 * sizeof(_Float16)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&cpk), (size_t)packed_rows(K) * Dp * 2 * sizeof(_Float16)));
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&csi), 2 * sizeof(float)));
         int r2;
         if ((r2 = pack_rows(centroids, K, D, reinterpret_cast<uint32_t *>(csi + 1), cpk, cn, csi, st))) return r2;
@@ -487,7 +487,7 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
             unsigned long long *best = nullptr;
             HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), (size_t)cn_rows * sizeof(float)));
             HIPCHK(hipMalloc(reinterpret_cast<void **>(&xsi), (size_t)cn_rows * sizeof(float)));
-            HIPCHK(hipMalloc(reinterpret_cast<void **>(&xpk), (size_t)cn_rows * Dp * 2 * sizeof(_Float16)));
+            HIPCHK(hipMalloc(reinterpret_cast<void **>(&xpk), (size_t)packed_rows(cn_rows) * Dp * 2 * sizeof(_Float16)));
             HIPCHK(hipMalloc(reinterpret_cast<void **>(&Dt), (size_t)cn_rows * sizeof(unsigned long long)));
             best = reinterpret_cast<unsigned long long *>(Dt);
             for (int64_t q0 = 0; q0 < nq; q0 += chunk) {
@@ -507,7 +507,7 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
         }
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), (size_t)tile * sizeof(float)));
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&xsi), (size_t)tile * sizeof(float)));
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xpk), (size_t)tile * Dp * 2 * sizeof(_Float16)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xpk), (size_t)packed_rows(tile) * Dp * 2 * sizeof(_Float16)));
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&Dt), (size_t)tile * K * sizeof(float)));
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&bm), (size_t)tile * nb * sizeof(float)));
         for (int64_t q0 = 0; q0 < nq; q0 += tile) {
