@@ -232,14 +232,16 @@ constexpr int SLD = 64 + 4;   // row stride (floats) of a wavefront's 32x64 outp
 // writes four rows of 256 contiguous bytes.  qb / cb: first query / centroid of the block;
 // cnw: the 64 centroid norms of the block (LDS).  EDGE = false skips all bounds checks (the
 // block lies inside Dt and K is a multiple of 4).
-template <bool EDGE>
+template <bool EDGE, int SROWS = 32>
 __device__ __forceinline__ void emit_block(const floatx16 (&acc)[2], float qr, float m2, const float *cnw,
                                            float *stage, int64_t qb, int64_t nq, int64_t cb, int64_t K,
-                                           float *__restrict__ Dt, float *__restrict__ bm, int nb)
+                                           float *__restrict__ Dt, int64_t ldt, float *__restrict__ bm, int nb)
 {
+    static_assert(SROWS == 32 || SROWS == 16, "the staging area holds 32 or 16 query rows");
     const int lane = threadIdx.x & 63;
     const int l32 = lane & 31, h = lane >> 5;
     const int sr = lane >> 4, sc = (lane & 15) * 4;
+    float4 d[2][4];
     float m = INFINITY;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
@@ -247,55 +249,70 @@ __device__ __forceinline__ void emit_block(const floatx16 (&acc)[2], float qr, f
         for (int g = 0; g < 4; ++g) {
             const int cl = j * 32 + 8 * g + 4 * h;          // centroid of element 4g inside the block
             const float4 cv = *reinterpret_cast<const float4 *>(&cnw[cl]);
-            float4 d;
-            d.x = fmaxf(fmaf(m2, acc[j][4 * g + 0], qr + cv.x), 0.f);
-            d.y = fmaxf(fmaf(m2, acc[j][4 * g + 1], qr + cv.y), 0.f);
-            d.z = fmaxf(fmaf(m2, acc[j][4 * g + 2], qr + cv.z), 0.f);
-            d.w = fmaxf(fmaf(m2, acc[j][4 * g + 3], qr + cv.w), 0.f);
+            float4 &e = d[j][g];
+            e.x = fmaxf(fmaf(m2, acc[j][4 * g + 0], qr + cv.x), 0.f);
+            e.y = fmaxf(fmaf(m2, acc[j][4 * g + 1], qr + cv.y), 0.f);
+            e.z = fmaxf(fmaf(m2, acc[j][4 * g + 2], qr + cv.z), 0.f);
+            e.w = fmaxf(fmaf(m2, acc[j][4 * g + 3], qr + cv.w), 0.f);
             if (EDGE) {
                 const int64_t c = cb + cl;
-                m = fminf(m, c + 0 < K ? d.x : INFINITY);
-                m = fminf(m, c + 1 < K ? d.y : INFINITY);
-                m = fminf(m, c + 2 < K ? d.z : INFINITY);
-                m = fminf(m, c + 3 < K ? d.w : INFINITY);
+                m = fminf(m, c + 0 < K ? e.x : INFINITY);
+                m = fminf(m, c + 1 < K ? e.y : INFINITY);
+                m = fminf(m, c + 2 < K ? e.z : INFINITY);
+                m = fminf(m, c + 3 < K ? e.w : INFINITY);
             } else {
-                m = fminf(fminf(m, d.x), fminf(d.y, fminf(d.z, d.w)));
+                m = fminf(fminf(m, e.x), fminf(e.y, fminf(e.z, e.w)));
             }
-            *reinterpret_cast<float4 *>(&stage[l32 * SLD + cl]) = d;
         }
     m = fminf(m, __shfl_xor(m, 32, WAVE));   // the other half holds the other 32 centroids
     const int64_t q = qb + l32, blk = cb / BMW;
     if (h == 0 && (!EDGE || (q < nq && blk < nb))) bm[q * nb + blk] = m;
-    wave_sync();
-    if (EDGE) {
-        const bool vec = (K & 3) == 0;
+    // through the staging area, SROWS query rows at a time (the lanes of the other rows sit a pass out)
 #pragma unroll
-        for (int it = 0; it < 8; ++it) {
-            const int r = it * 4 + sr;
-            const int64_t qq = qb + r, c = cb + sc;
-            const float4 d = *reinterpret_cast<const float4 *>(&stage[r * SLD + sc]);
-            if (qq < nq) {
-                float *rowp = Dt + qq * K;
-                if (vec && c + 3 < K) {
-                    *reinterpret_cast<float4 *>(rowp + c) = d;
-                } else {
-                    const float dv[4] = {d.x, d.y, d.z, d.w};
+    for (int pass = 0; pass < 32 / SROWS; ++pass) {
+        if (SROWS == 32 || (l32 / SROWS) == pass) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (c + e < K) rowp[c + e] = dv[e];
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<float4 *>(&stage[(l32 % SROWS) * SLD + j * 32 + 8 * g + 4 * h]) = d[j][g];
+        }
+        wave_sync();
+        const int64_t qp = qb + pass * SROWS;
+        if (EDGE) {
+            const bool vec = (K & 3) == 0;
+#pragma unroll
+            for (int it = 0; it < SROWS / 4; ++it) {
+                const int r = it * 4 + sr;
+                const int64_t qq = qp + r, c = cb + sc;
+                const float4 v = *reinterpret_cast<const float4 *>(&stage[r * SLD + sc]);
+                if (qq < nq) {
+                    float *rowp = Dt + qq * ldt;
+                    if (vec && c + 3 < K) {
+                        *reinterpret_cast<float4 *>(rowp + c) = v;
+                    } else {
+                        const float dv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (c + e < K) rowp[c + e] = dv[e];
+                    }
                 }
             }
-        }
-    } else {
-        float *p = Dt + (qb + sr) * K + cb + sc;
+        } else {
+            float *p = Dt + (qp + sr) * ldt + cb + sc;
 #pragma unroll
-        for (int it = 0; it < 8; ++it) {
-            *reinterpret_cast<float4 *>(p) = *reinterpret_cast<const float4 *>(&stage[(it * 4 + sr) * SLD + sc]);
-            p += 4 * K;
+            for (int it = 0; it < SROWS / 4; ++it) {
+                *reinterpret_cast<float4 *>(p) = *reinterpret_cast<const float4 *>(&stage[(it * 4 + sr) * SLD + sc]);
+                p += 4 * ldt;
+            }
         }
+        wave_sync();
     }
-    wave_sync();
 }
+
+// Row stride of the distance matrix Dt in floats.  Unpadded: padding the rows (by 128 bytes up
+// to 16 KB) made the tile stores slower on the MI355X, not faster.
+__host__ __device__ inline int64_t dt_stride(int64_t K) { return K; }
 
 // Dt[q][j] = max(0, qn[q] + cn[j] - 2 <Q[q], C[j]>), and bm[q][b] = the minimum
 // of Dt[q][64b .. 64b+63] (each wavefront's 64-centroid quadrant gives one block
@@ -304,7 +321,7 @@ __device__ __forceinline__ void emit_block(const floatx16 (&acc)[2], float qr, f
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void coarse_gemm_kernel(
     const _Float16 *__restrict__ Qp, const float *__restrict__ qn, const float *__restrict__ qsi, int64_t nq,
     const _Float16 *__restrict__ Cp, const float *__restrict__ cn, const float *__restrict__ csi, int64_t K,
-    int Dp, float *__restrict__ Dt, float *__restrict__ bm, int nb, int tiles_q)
+    int Dp, float *__restrict__ Dt, int64_t ldt, float *__restrict__ bm, int nb, int tiles_q)
 {
     // two operand buffers of 256 rows x 64 bytes, each reused as the output staging of two wavefronts
     __shared__ __attribute__((aligned(16))) float ops0[2 * 32 * SLD];
@@ -327,9 +344,186 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         const int64_t qb = q0 + wq + i * 32, q = qb + l32;
         const float qr = q < nq ? qn[q] : 0.f;
         const float m2 = q < nq ? m2c * qsi[q] : 0.f;
-        if (interior) emit_block<false>(acc[i], qr, m2, cns + wc, stage, qb, nq, c0 + wc, K, Dt, bm, nb);
-        else emit_block<true>(acc[i], qr, m2, cns + wc, stage, qb, nq, c0 + wc, K, Dt, bm, nb);
+        if (interior) emit_block<false>(acc[i], qr, m2, cns + wc, stage, qb, nq, c0 + wc, K, Dt, ldt, bm, nb);
+        else emit_block<true>(acc[i], qr, m2, cns + wc, stage, qb, nq, c0 + wc, K, Dt, ldt, bm, nb);
     }
+}
+
+// s_waitcnt immediate that waits until at most n vector-memory operations of the wavefront are
+// outstanding (they complete in issue order) and leaves the other counters alone.
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+// Large batches, STAGES = packed_dim / 16 known at compile time: a workgroup keeps ONE query
+// tile and sweeps `tiles_per_wg` consecutive centroid tiles.  Its query operand never passes
+// through LDS: every lane holds the fragments of its query rows for all stages in registers
+// (16 STAGES of them), so per centroid tile only the 128 centroid rows are copied
+// (global -> LDS, 8 KB a stage) into a ring of RING buffers, PD = RING - 1 stages ahead (a copy
+// takes a few microseconds to land, several steps' worth of MFMA work), and
+// the ring keeps running across tiles: the copies of the next tile's first stages are in
+// flight during the epilogue of the current one.  The distance stores of a workgroup walk
+// along its 128 rows of Dt, tile after tile.  STAGES is a multiple of RING, so stage s of
+// every tile uses buffer s % RING and each step names its buffer statically (separate LDS
+// objects, see gemm_tile).  Same k order and products as gemm_tile: identical results.
+//
+// Waiting for a copy with operations issued after it still in flight relies on in-order
+// completion; the counts below are the vector-memory operations a wavefront issues between a
+// copy and the step that consumes it, or a lower bound of them (2 copies a step, at least 16
+// stores an epilogue).  Only whole tiles are handled (nq a multiple of 128 here, K a multiple
+// of 128): the host gives the last, partial query tile to coarse_gemm_kernel.  The workgroup barrier of a step orders LDS traffic only (operands arrive by copies
+// that each wavefront has waited for, nothing else is shared), so it is issued without the
+// global-memory fence of __syncthreads, which would drain the queue at every step.
+constexpr int SWEEP_IL = 2;   // workgroups interleaved over adjacent centroid tiles
+
+template <int STAGES>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void coarse_gemm_sweep_kernel(
+    const _Float16 *__restrict__ Qp, const float *__restrict__ qn, const float *__restrict__ qsi, int64_t nq,
+    const _Float16 *__restrict__ Cp, const float *__restrict__ cn, const float *__restrict__ csi, int64_t K,
+    float *__restrict__ Dt, int64_t ldt, float *__restrict__ bm, int nb, int tiles_q, int tiles_c, int tiles_per_wg)
+{
+    typedef const __attribute__((address_space(1))) void *gptr_t;
+    typedef __attribute__((address_space(3))) void *lptr_t;
+    constexpr int RING = STAGES <= 6 ? STAGES : 4;        // 6 stages: the ring holds a whole tile
+    static_assert(STAGES % RING == 0 && STAGES >= RING && RING <= 6, "stage s of every tile must use buffer s % RING");
+    constexpr int PD = RING - 1;
+    constexpr int Dp = STAGES * DK;
+    constexpr int SLOT = GT * ROWF;                        // floats per ring buffer: 128 rows x 64 bytes
+    constexpr int EPI_STORES = 16;                         // distance stores of an interior epilogue (a lower bound of its stores)
+    __shared__ __attribute__((aligned(16))) float ring0[SLOT];
+    __shared__ __attribute__((aligned(16))) float ring1[SLOT];
+    __shared__ __attribute__((aligned(16))) float ring2[SLOT];
+    __shared__ __attribute__((aligned(16))) float ring3[RING > 3 ? SLOT : 4];
+    __shared__ __attribute__((aligned(16))) float ring4[RING > 4 ? SLOT : 4];
+    __shared__ __attribute__((aligned(16))) float ring5[RING > 5 ? SLOT : 4];
+    __shared__ __attribute__((aligned(16))) float stage_all[4 * 16 * SLD];   // 16 query rows per wavefront at a time
+    __shared__ __attribute__((aligned(16))) float cns[2][GT];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, h = lane >> 5;
+    const int wq = (wave >> 1) * 64, wc = (wave & 1) * 64;
+
+    // workgroup -> (query tile, range of centroid tiles): XCD x = b % 8 owns query tiles x, x+8, ...
+    const int tq_per = (tiles_q + N_XCD - 1) / N_XCD;
+    const int xcd = (int)(blockIdx.x % N_XCD);
+    // IL workgroups with consecutive ids share a query tile and take centroid tiles k, k + IL,
+    // k + 2 IL, ... of a group: they start together and advance at the same rate, so at any time
+    // they write IL adjacent 512-byte pieces of the same rows of Dt (longer runs for the L2
+    // write-back and the DRAM pages).  Step j of the workgroup is centroid tile tb + j * IL.
+    constexpr int IL = SWEEP_IL;
+    const int64_t local = blockIdx.x / N_XCD;
+    const int k_il = (int)(local % IL);
+    const int64_t rest = local / IL;
+    const int tq = (int)(rest % tq_per) * N_XCD + xcd;
+    if (tq >= tiles_q) return;
+    const int tb = (int)(rest / tq_per) * tiles_per_wg * IL + k_il;
+    const int t_begin = 0;
+    int t_end = tb < tiles_c ? (tiles_c - tb + IL - 1) / IL : 0;      // steps inside the matrix
+    if (t_end > tiles_per_wg) t_end = tiles_per_wg;
+    if (t_begin >= t_end) return;
+    const int64_t q0 = (int64_t)tq * GT;
+
+    // this wave's two copies per stage: rows 32 wave + 16 n + lane / 4 of the centroid tile
+    const int rl = wave * 32 + (lane >> 2);
+    const int fl = (lane & 3) ^ ((lane >> 4) & 3);         // ((row >> 2) & 3 is the same for both rows)
+    const float *cbase = reinterpret_cast<const float *>(Cp) + (int64_t)rl * Dp + fl * 4;
+    auto slot_of = [&](int s) -> float * {
+        const int r = s % RING;
+        return r == 0 ? ring0 : r == 1 ? ring1 : r == 2 ? ring2 : r == 3 ? ring3 : r == 4 ? ring4 : ring5;
+    };
+    // copy stage s (may be >= STAGES: a stage of the following tile) of tile t; past the range the
+    // last tile is copied again (never read), so that the number of copies per step is fixed
+    auto issue = [&](int t, int s) {
+        if (s >= STAGES) { s -= STAGES; ++t; }
+        if (t >= t_end) t = t_end - 1;
+        const float *src = cbase + (int64_t)(tb + t * IL) * GT * Dp + s * DK;
+        float *dst = slot_of(s) + wave * 512;
+#pragma nounroll
+        for (int n = 0; n < 2; ++n)
+            __builtin_amdgcn_global_load_lds((gptr_t)(src + (int64_t)n * 16 * Dp), (lptr_t)(dst + n * 256), 16, 0, 0);
+    };
+
+#pragma unroll
+    for (int s = 0; s < PD; ++s) issue(t_begin, s);
+
+    // query fragments: for stage s and block i the 32 bytes [hi | lo] of row wq + 32 i + l32, half h
+    gu32x4 afr[STAGES][2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const gu32x4 *row = reinterpret_cast<const gu32x4 *>(reinterpret_cast<const float *>(Qp) + (q0 + wq + i * 32 + l32) * Dp) + 2 * h;
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s) {
+            afr[s][i][0] = row[s * 4 + 0];
+            afr[s][i][1] = row[s * 4 + 1];
+        }
+    }
+    float qr[2], m2[2];
+    {
+        const float m2c = -2.f * csi[0];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int64_t q = q0 + wq + i * 32 + l32;
+            qr[i] = qn[q];
+            m2[i] = m2c * qsi[q];
+        }
+    }
+    cns[t_begin & 1][tid & (GT - 1)] = cn[(int64_t)tb * GT + (tid & (GT - 1))];
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // fragments and the first copies are in: the counts below start from an empty queue
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    float *stage = stage_all + wave * (16 * SLD);
+
+    for (int t = t_begin; t < t_end; ++t) {
+        const int64_t c0 = (int64_t)(tb + t * IL) * GT;
+        float cn_next = 0.f;
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s) {
+            // operations issued after the copy of this stage: the copies of the PD - 1 stages after it,
+            // the norm load when it was issued in between, the epilogue stores when it lies in between
+            // (the tile's one norm load is left out of the count: wherever the compiler places it,
+            // waiting for one operation more than needed is harmless)
+            constexpr int COPIES = 2 * (PD - 1);
+            if (s < PD) __builtin_amdgcn_s_waitcnt(vmcnt_imm(COPIES + EPI_STORES));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(COPIES));
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            issue(t, s + PD);
+            // norms of the next tile, parked in a register until the middle of this one (an
+            // unconditional load with a clamped index: nothing forces the wave to wait for it here)
+            const int64_t cnx = c0 + (int64_t)IL * GT + (tid & (GT - 1));
+            if (s == 0) cn_next = cn[cnx < K ? cnx : K - 1];
+            if (s == STAGES / 2) cns[(t + 1) & 1][tid & (GT - 1)] = cnx < K ? cn_next : 0.f;
+            const float *Bs = slot_of(s);
+            gu32x4 b[2][2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int rb = wc + j * 32 + l32;
+#pragma unroll
+                for (int p = 0; p < 2; ++p)
+                    b[j][p] = *reinterpret_cast<const gu32x4 *>(&Bs[rb * ROWF + (((2 * h + p) ^ ((rb >> 2) & 3)) << 2)]);
+            }
+#pragma unroll
+            for (int e = 0; e < 3; ++e)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) acc[i][j] = mfma3(b[j], afr[s][i], acc[i][j], e);
+        }
+        const float *cnw = cns[t & 1] + wc;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            emit_block<false, 16>(acc[i], qr[i], m2[i], cnw, stage, q0 + wq + i * 32, nq, c0 + wc, K, Dt, ldt, bm, nb);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // no copy into LDS may outlive the workgroup
 }
 
 // The same for small batches (latency mode): a workgroup takes 32 queries x 256 centroids, all
@@ -343,7 +537,7 @@ constexpr int SKBUF = (SKQ + SKC) * ROWF;   // floats per operand buffer
 __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
     const _Float16 *__restrict__ Qp, const float *__restrict__ qn, const float *__restrict__ qsi, int64_t nq,
     const _Float16 *__restrict__ Cp, const float *__restrict__ cn, const float *__restrict__ csi, int64_t K,
-    int Dp, float *__restrict__ Dt, float *__restrict__ bm, int nb, int tiles_q)
+    int Dp, float *__restrict__ Dt, int64_t ldt, float *__restrict__ bm, int nb, int tiles_q)
 {
     typedef const __attribute__((address_space(1))) void *gptr_t;
     typedef __attribute__((address_space(3))) void *lptr_t;
@@ -413,8 +607,8 @@ __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
     const float qr = q < nq ? qn[q] : 0.f;
     const float m2 = q < nq ? m2c * qsi[q] : 0.f;
     const bool interior = q0 + SKQ <= nq && c0 + SKC <= K && (K & 3) == 0;
-    if (interior) emit_block<false>(acc, qr, m2, cns + wc, stage, q0, nq, c0 + wc, K, Dt, bm, nb);
-    else emit_block<true>(acc, qr, m2, cns + wc, stage, q0, nq, c0 + wc, K, Dt, bm, nb);
+    if (interior) emit_block<false>(acc, qr, m2, cns + wc, stage, q0, nq, c0 + wc, K, Dt, ldt, bm, nb);
+    else emit_block<true>(acc, qr, m2, cns + wc, stage, q0, nq, c0 + wc, K, Dt, ldt, bm, nb);
 }
 
 // Nearest centroid only (P = 1): the same tile product, reduced on the fly to
@@ -485,7 +679,7 @@ __global__ __launch_bounds__(256) void argmin_unpack_kernel(const unsigned long 
 //      elements of the listed blocks (at most 2P*64), read from Dt.
 // blist is dynamic LDS of 2*P ints.
 template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void probe_select_kernel(const float *__restrict__ Dt,
+__global__ __launch_bounds__(BLOCK) void probe_select_kernel(const float *__restrict__ Dt, int64_t ldt,
                                                              const float *__restrict__ bm, int64_t K,
                                                              int nb, int P,
                                                              int32_t *__restrict__ probe_id,
@@ -495,7 +689,7 @@ __global__ __launch_bounds__(BLOCK) void probe_select_kernel(const float *__rest
     __shared__ uint32_t nflag_s;
     extern __shared__ int blist[];
     const int64_t q = blockIdx.x;
-    const float *row = Dt + q * K;
+    const float *row = Dt + q * ldt;
     const float *bmr = bm + q * nb;
     auto keyb = [bmr](int64_t b) { return float_key(bmr[b]); };
     const uint32_t nselb = P < nb ? (uint32_t)P : (uint32_t)nb;

@@ -117,11 +117,12 @@ int pack_rows(const float *X, int64_t n, int D, uint32_t *gmax, _Float16 *P, flo
 int launch_coarse(const _Float16 *xp, const float *xn, const float *xsi, int64_t nq, const _Float16 *Cp,
                   const float *cn, const float *csi, int64_t K, int Dp, float *Dt, float *bm, hipStream_t st)
 {
+    const int64_t ldt = dt_stride(K);
     const int nb = (int)((K + BMW - 1) / BMW);
     if (nq <= 2 * SKQ) {   // small batch: 32-query tiles
         int tiles_q = (int)((nq + SKQ - 1) / SKQ);
         int64_t grid = tiles_q * ((K + SKC - 1) / SKC);
-        coarse_gemm_skinny_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xp, xn, xsi, nq, Cp, cn, csi, K, Dp, Dt, bm, nb, tiles_q);
+        coarse_gemm_skinny_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xp, xn, xsi, nq, Cp, cn, csi, K, Dp, Dt, ldt, bm, nb, tiles_q);
         LAUNCHCHK("coarse_gemm_skinny_kernel");
         return IVF_OK;
     }
@@ -129,7 +130,23 @@ int launch_coarse(const _Float16 *xp, const float *xn, const float *xsi, int64_t
     int64_t tiles_c = (K + GT - 1) / GT;
     int64_t grid = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * tiles_c;
     if (grid >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
-    coarse_gemm_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xp, xn, xsi, nq, Cp, cn, csi, K, Dp, Dt, bm, nb, tiles_q);
+    const int stages = Dp / DK;
+    if ((stages == 6 || stages == 8) && K % GT == 0) {
+        // Query tile held in registers, centroid tiles swept.  The kernel works on whole tiles: the
+        // rows of a partial last query tile are computed too, into the padding every per-query
+        // buffer of the coarse stage carries up to a multiple of the tile height.
+        const int per_wg = 64;
+        const int64_t groups = (tiles_c + (int64_t)per_wg * SWEEP_IL - 1) / ((int64_t)per_wg * SWEEP_IL);
+        const int64_t g2 = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * groups * SWEEP_IL;
+        if (g2 >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
+        if (stages == 6)
+            coarse_gemm_sweep_kernel<6><<<dim3((unsigned)g2), dim3(256), 0, st>>>(xp, xn, xsi, (int64_t)tiles_q * GT, Cp, cn, csi, K, Dt, ldt, bm, nb, tiles_q, (int)tiles_c, per_wg);
+        else
+            coarse_gemm_sweep_kernel<8><<<dim3((unsigned)g2), dim3(256), 0, st>>>(xp, xn, xsi, (int64_t)tiles_q * GT, Cp, cn, csi, K, Dt, ldt, bm, nb, tiles_q, (int)tiles_c, per_wg);
+        LAUNCHCHK("coarse_gemm_sweep_kernel");
+        return IVF_OK;
+    }
+    coarse_gemm_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xp, xn, xsi, nq, Cp, cn, csi, K, Dp, Dt, ldt, bm, nb, tiles_q);
     LAUNCHCHK("coarse_gemm_kernel");
     return IVF_OK;
 }
@@ -140,9 +157,9 @@ int launch_probe_select(const float *Dt, const float *bm, int64_t nq, int64_t K,
     const int nb = (int)((K + BMW - 1) / BMW);
     const size_t lds = (size_t)2 * P * sizeof(int);
     if (P >= 1024)
-        probe_select_kernel<1024><<<dim3((unsigned)nq), dim3(1024), lds, st>>>(Dt, bm, K, nb, P, pid, pd);
+        probe_select_kernel<1024><<<dim3((unsigned)nq), dim3(1024), lds, st>>>(Dt, dt_stride(K), bm, K, nb, P, pid, pd);
     else
-        probe_select_kernel<256><<<dim3((unsigned)nq), dim3(256), lds, st>>>(Dt, bm, K, nb, P, pid, pd);
+        probe_select_kernel<256><<<dim3((unsigned)nq), dim3(256), lds, st>>>(Dt, dt_stride(K), bm, K, nb, P, pid, pd);
     LAUNCHCHK("probe_select_kernel");
     return IVF_OK;
 }
@@ -329,13 +346,14 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
     const int merge_n = n_lists * k, merge_pow2 = next_pow2(merge_n);
 
     int rc;
-    if ((rc = ensure(ix->dt, (size_t)tile * K * sizeof(float)))) return rc;
+    const size_t tile_pad = (size_t)packed_rows(tile);   // the GEMM may write whole tiles of rows
+    if ((rc = ensure(ix->dt, tile_pad * dt_stride(K) * sizeof(float)))) return rc;
     const int64_t nb = (K + BMW - 1) / BMW;
-    if ((rc = ensure(ix->bm, (size_t)tile * nb * sizeof(float)))) return rc;
-    if ((rc = ensure(ix->qn, (size_t)tile * sizeof(float)))) return rc;
+    if ((rc = ensure(ix->bm, tile_pad * nb * sizeof(float)))) return rc;
+    if ((rc = ensure(ix->qn, tile_pad * sizeof(float)))) return rc;
     const int Dp = packed_dim(D);
     if ((rc = ensure(ix->qpk, (size_t)packed_rows(tile) * Dp * 2 * sizeof(_Float16)))) return rc;
-    if ((rc = ensure(ix->qsi, (size_t)tile * sizeof(float)))) return rc;
+    if ((rc = ensure(ix->qsi, tile_pad * sizeof(float)))) return rc;
     if ((rc = ensure(ix->probe_id, (size_t)tile * P * sizeof(int32_t)))) return rc;
     if ((rc = ensure(ix->probe_d, (size_t)tile * P * sizeof(float)))) return rc;
     if ((rc = ensure(ix->desc, (size_t)tile * S * sizeof(SubDesc)))) return rc;
@@ -390,10 +408,10 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
         int64_t *ns = n_scanned_out ? n_scanned_out + q0 : nullptr;
         if (PL > 4096)
             score_prune_kernel<1024><<<dim3((unsigned)n), dim3(1024), sp_lds, st>>>(
-                Dt, K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, desc, ks, ns);
+                Dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, desc, ks, ns);
         else
             score_prune_kernel<256><<<dim3((unsigned)n), dim3(256), sp_lds, st>>>(
-                Dt, K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, desc, ks, ns);
+                Dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, desc, ks, ns);
         LAUNCHCHK("score_prune_kernel");
         if ((rc = mark(3))) return rc;
         if ((rc = mark(4))) return rc;
@@ -505,11 +523,12 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
             HIPCHK(hipStreamSynchronize(st));
             return IVF_OK;
         }
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), (size_t)tile * sizeof(float)));
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xsi), (size_t)tile * sizeof(float)));
+        const size_t tile_pad = (size_t)packed_rows(tile);   // the GEMM may write whole tiles of rows
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), tile_pad * sizeof(float)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xsi), tile_pad * sizeof(float)));
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&xpk), (size_t)packed_rows(tile) * Dp * 2 * sizeof(_Float16)));
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&Dt), (size_t)tile * K * sizeof(float)));
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&bm), (size_t)tile * nb * sizeof(float)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&Dt), tile_pad * dt_stride(K) * sizeof(float)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&bm), tile_pad * nb * sizeof(float)));
         for (int64_t q0 = 0; q0 < nq; q0 += tile) {
             const int64_t n = (nq - q0 < tile) ? nq - q0 : tile;
             if ((r2 = pack_rows(x + q0 * D, n, D, nullptr, xpk, xn, xsi, st))) return r2;

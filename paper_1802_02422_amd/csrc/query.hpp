@@ -24,7 +24,7 @@ struct SubDesc {
 // Dynamic LDS: P*L keys + P probe ids + P probe distances + P alphas.
 template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void score_prune_kernel(
-    const float *__restrict__ Dt, int64_t K, const int32_t *__restrict__ probe_id,
+    const float *__restrict__ Dt, int64_t ldt, int64_t K, const int32_t *__restrict__ probe_id,
     const float *__restrict__ probe_d, int P, int L, const int32_t *__restrict__ nbr,
     const float *__restrict__ cst, const float *__restrict__ alpha, int S,
     const uint4 *__restrict__ sub_info,
@@ -39,7 +39,7 @@ __global__ __launch_bounds__(BLOCK) void score_prune_kernel(
     float *pd = reinterpret_cast<float *>(dyn + PL + P);
     float *pa = reinterpret_cast<float *>(dyn + PL + 2 * P);
     const int64_t q = blockIdx.x;
-    const float *row = Dt + q * K;
+    const float *row = Dt + q * ldt;
     for (int p = threadIdx.x; p < P; p += BLOCK) {
         const int32_t r = probe_id[q * P + p];
         pid[p] = r;
