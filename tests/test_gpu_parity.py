@@ -42,6 +42,38 @@ def test_coarse_topk_matches_bruteforce(tiny):
         assert (np.abs(gd - d_true) <= np.maximum(1e-4 * d_true, at[:, None])).all()
 
 
+@pytest.mark.parametrize("D,K,nq", [(20, 300, 1), (96, 1280, 65), (100, 1000, 128), (128, 1024, 200), (96, 2560, 300)])
+def test_coarse_distances_within_fp32_bound_for_all_kernel_variants(D, K, nq):
+    """Shapes that reach every variant of the coarse kernel (small batch, generic tile with a
+    padded width, swept tiles with a partial last query tile), rows of very different
+    magnitude, exact duplicates: every returned distance is within 16 u (|q|^2 + max |c|^2) of
+    the fp64 value, and the P returned regions are the exact ones up to ties inside that bound."""
+    print("case: coarse variants", D, K, nq, flush=True)
+    rng = np.random.default_rng(1000 * D + K + nq)
+    C = rng.standard_normal((K, D)) * np.exp2(rng.integers(-6, 1, size=(K, 1)))
+    Q = rng.standard_normal((nq, D)) * np.exp2(rng.integers(-8, 9, size=(nq, 1)))
+    Q[0] = C[K // 2]                                     # a query that is a centroid: distance 0
+    C, Q = C.astype(np.float32), Q.astype(np.float32)
+    P = min(K, 64)
+    gid, gd = ivf.ivf_coarse_topk(torch.from_numpy(C).cuda(), torch.from_numpy(Q).cuda(), P)
+    gid, gd = gid.cpu().numpy(), gd.cpu().numpy()
+    c64, q64 = C.astype(np.float64), Q.astype(np.float64)
+    exact = (q64 ** 2).sum(1)[:, None] + (c64 ** 2).sum(1)[None, :] - 2.0 * q64 @ c64.T
+    exact = np.maximum(exact, 0.0)
+    u = 2.0 ** -24
+    tol = 16 * u * ((q64 ** 2).sum(1) + (c64 ** 2).sum(1).max())
+    err = np.abs(gd - np.take_along_axis(exact, gid.astype(np.int64), axis=1))
+    print("  max error / tolerance: %.3f" % (err / tol[:, None]).max(), flush=True)
+    assert (err <= tol[:, None]).all()
+    assert gd[0].min() <= tol[0] and (gd >= 0).all()
+    kth = np.sort(exact, axis=1)[:, P - 1]
+    for q in range(nq):
+        assert len(set(gid[q].tolist())) == P and (np.diff(gid[q]) > 0).all()      # distinct, ascending ids
+        assert (exact[q, gid[q]] <= kth[q] + 2 * tol[q]).all()                       # nothing beyond the boundary
+        must = np.nonzero(exact[q] < kth[q] - 2 * tol[q])[0]                         # clearly inside: all present
+        assert np.isin(must, gid[q]).all()
+
+
 def test_search_tiny_all_stages(tiny_gpu):
     spec, ix, Q, X, handle = tiny_gpu
     print("case: search tiny", spec, flush=True)
