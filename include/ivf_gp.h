@@ -85,7 +85,9 @@ void ivf_free_index(ivf_index *index);
 /*
  * Upper bound in bytes for the scratch the handle may hold for the
  * query-by-centroid distance tile of stage 1 (default 8 GiB).  Larger batches
- * are processed in several tiles of queries.  Host call.
+ * are processed in several tiles of queries.  The tile is allocated in whole
+ * blocks of 256 query rows, so it can exceed the bound by up to 255 rows of
+ * 4*K bytes.  Host call.
  */
 int ivf_set_scratch_limit(ivf_index *index, int64_t bytes);
 
@@ -106,7 +108,11 @@ int ivf_set_scratch_limit(ivf_index *index, int64_t bytes);
  * out_ids [nq][k] int32 and out_dists [nq][k] fp32 (estimated squared L2
  * distance); rows with fewer than k candidates are padded with id -1 and
  * +inf.  1 <= nprobe <= min(K, 4096), 0 < prune_frac <= 1,
- * 1 <= k <= IVF_MAX_K_RESULTS, nprobe*L <= 32000.  All arithmetic is fp32.
+ * 1 <= k <= IVF_MAX_K_RESULTS, nprobe*L <= 32000.  All results are fp32 and
+ * carry fp32 rounding errors; the inner products <q, c> of stage 1 are
+ * formed on the fp16 matrix units from operands split into a high and a low
+ * half (22 significant bits) and accumulated in fp32, which is as accurate
+ * as an fp32 dot product.
  * Asynchronous on hip_stream; the handle's scratch is reused by every call,
  * so calls on one handle must not overlap.
  */
