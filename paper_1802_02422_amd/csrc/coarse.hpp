@@ -714,4 +714,98 @@ __global__ __launch_bounds__(BLOCK) void probe_select_kernel(const float *__rest
                                });
 }
 
+// The same selection with the keys held in LDS, for nb <= PS_NB_MAX block minima and
+// P <= PS_P_MAX: the block minima are read once (not once per radix pass), and of the flagged
+// blocks' elements only those at or below the block threshold t are kept (t is the P-th
+// smallest block minimum, so the P closest centroids are among them; with randomly numbered
+// centroids little more than P survive), compacted in ascending centroid id, and selected
+// from LDS.  A query with more than PS_CAP survivors (duplicated centroids) takes the
+// global-memory path of probe_select_kernel.  Dynamic LDS: 2P + max(nb, 2 PS_CAP) words.
+constexpr int PS_NB_MAX = 16384, PS_P_MAX = 256, PS_CAP = 4096, PS_IPT = 2 * PS_P_MAX * BMW / 1024;
+
+__global__ __launch_bounds__(1024) void probe_select_lds_kernel(const float *__restrict__ Dt, int64_t ldt,
+                                                                const float *__restrict__ bm, int64_t K,
+                                                                int nb, int P,
+                                                                int32_t *__restrict__ probe_id,
+                                                                float *__restrict__ probe_d)
+{
+    constexpr int BLOCK = 1024;
+    __shared__ SelectShared sh;
+    __shared__ uint32_t nflag_s;
+    extern __shared__ __attribute__((aligned(16))) int ps_dyn[];
+    int *blist = ps_dyn;                                           // 2P flagged blocks
+    uint32_t *keys = reinterpret_cast<uint32_t *>(ps_dyn + 2 * P); // nb block-minimum keys, then the survivors
+    const int tid = threadIdx.x;
+    const int64_t q = blockIdx.x;
+    const float *row = Dt + q * ldt;
+    const float *bmr = bm + q * nb;
+    for (int i = tid; i < nb; i += BLOCK) keys[i] = float_key(bmr[i]);
+    __syncthreads();
+    auto keyb = [keys](int64_t b) { return keys[b]; };
+    const uint32_t nselb = P < nb ? (uint32_t)P : (uint32_t)nb;
+    uint32_t t, needb;
+    block_radix_select<BLOCK>(keyb, nb, nselb, sh, t, needb);
+    uint32_t nflag = block_emit_selected_runs<BLOCK>(keyb, nb, t, (uint32_t)P, sh,
+                                                     [&](uint32_t pos, int64_t b, uint32_t) { blist[pos] = (int)b; });
+    if (tid == 0) nflag_s = nflag;
+    __syncthreads();                                               // blist complete, the block keys are dead
+    nflag = nflag_s;
+    const uint32_t tf = nb >= P ? t : 0xFFFFFFFFu;                 // fewer blocks than P: no filter
+    const int n_c = (int)nflag * BMW;
+    const int ipt = (n_c + BLOCK - 1) / BLOCK;                     // <= PS_IPT
+    const int i0 = tid * ipt;
+    uint32_t kv[PS_IPT];
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int j = 0; j < PS_IPT; ++j) {
+        const int v = i0 + j;
+        uint32_t k = 0xFFFFFFFFu;
+        if (j < ipt && v < n_c) {
+            const int64_t c = (int64_t)blist[v >> 6] * BMW + (v & 63);
+            if (c < K) k = float_key(row[c]);
+        }
+        kv[j] = k;
+    }
+#pragma unroll
+    for (int j = 0; j < PS_IPT; ++j) cnt += (kv[j] <= tf && kv[j] != 0xFFFFFFFFu) ? 1u : 0u;
+    uint32_t total;
+    const uint32_t exc = block_exclusive_scan<BLOCK>(cnt, sh.scan, total);
+    if (total > (uint32_t)PS_CAP || total < (uint32_t)P) {          // uniform; the second cannot happen for nb >= P
+        auto key = [&](int64_t v) {
+            const int64_t c = (int64_t)blist[v >> 6] * BMW + (v & 63);
+            return c < K ? float_key(row[c]) : 0xFFFFFFFFu;
+        };
+        uint32_t pivot, need;
+        block_radix_select<BLOCK>(key, (int64_t)n_c, (uint32_t)P, sh, pivot, need);
+        block_emit_selected<BLOCK>(key, (int64_t)n_c, (uint32_t)P, pivot, need, sh,
+                                   [&](uint32_t pos, int64_t v, uint32_t k) {
+                                       probe_id[q * P + pos] = blist[v >> 6] * BMW + (int)(v & 63);
+                                       probe_d[q * P + pos] = key_float(k);
+                                   });
+        return;
+    }
+    uint32_t *sk = keys;
+    int *si = reinterpret_cast<int *>(keys + PS_CAP);
+    {
+        uint32_t at = exc;
+#pragma unroll
+        for (int j = 0; j < PS_IPT; ++j)
+            if (kv[j] <= tf && kv[j] != 0xFFFFFFFFu) {
+                const int v = i0 + j;
+                sk[at] = kv[j];
+                si[at] = blist[v >> 6] * BMW + (v & 63);
+                ++at;
+            }
+    }
+    __syncthreads();
+    auto skey = [sk](int64_t i) { return sk[i]; };
+    uint32_t pivot, need;
+    block_radix_select<BLOCK>(skey, (int64_t)total, (uint32_t)P, sh, pivot, need);
+    block_emit_selected_runs<BLOCK>(skey, (int)total, pivot, need, sh,
+                                    [&](uint32_t pos, int64_t i, uint32_t k) {
+                                        probe_id[q * P + pos] = si[i];
+                                        probe_d[q * P + pos] = key_float(k);
+                                    });
+}
+
 }  // namespace ivf

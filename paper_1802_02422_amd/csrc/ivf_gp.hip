@@ -156,6 +156,15 @@ int launch_probe_select(const float *Dt, const float *bm, int64_t nq, int64_t K,
 {
     const int nb = (int)((K + BMW - 1) / BMW);
     const size_t lds = (size_t)2 * P * sizeof(int);
+    if (P <= PS_P_MAX && nb <= PS_NB_MAX && nq > 64) {   // keys in LDS (throughput path)
+        const size_t lds2 = ((size_t)2 * P + (nb > 2 * PS_CAP ? nb : 2 * PS_CAP)) * sizeof(int);
+        if (lds2 > 48 * 1024)
+            HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&probe_select_lds_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2));
+        probe_select_lds_kernel<<<dim3((unsigned)nq), dim3(1024), lds2, st>>>(Dt, dt_stride(K), bm, K, nb, P, pid, pd);
+        LAUNCHCHK("probe_select_lds_kernel");
+        return IVF_OK;
+    }
     if (P >= 1024)
         probe_select_kernel<1024><<<dim3((unsigned)nq), dim3(1024), lds, st>>>(Dt, dt_stride(K), bm, K, nb, P, pid, pd);
     else

@@ -8,10 +8,25 @@
 namespace ivf {
 
 struct SelectShared {
-    uint32_t hist[256];
+    uint32_t hist[4][256];   // one histogram per radix pass
     uint32_t scan[16];
-    uint32_t pick[2];
+    uint32_t pick[4][2];
 };
+
+// hist[bin] += 1 for the calling lanes.  Keys that share their leading bytes (distances of one
+// query) put whole wavefronts into one bin of the first passes; 64 atomics on one LDS word are
+// executed one after the other, so a wavefront whose lanes all agree adds its population count once.
+__device__ __forceinline__ void hist_add(uint32_t *hist, uint32_t bin)
+{
+    const uint32_t b0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)bin);
+    const uint64_t active = __ballot(true), same = __ballot(bin == b0);
+    if (same == active) {
+        if (__builtin_amdgcn_mbcnt_hi((uint32_t)(active >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)active, 0u)) == 0)
+            atomicAdd(&hist[b0], (uint32_t)__popcll(active));
+    } else {
+        atomicAdd(&hist[bin], 1u);
+    }
+}
 
 // Finds the key value `pivot` of the nsel-th smallest item and the number
 // `need` of items equal to pivot that belong to the selection (those at the
@@ -22,9 +37,12 @@ __device__ void block_radix_select(KeyFn key, int64_t n, uint32_t nsel, SelectSh
 {
     const int tid = threadIdx.x;
     uint32_t prefix = 0, mask = 0, remaining = nsel;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        for (int i = tid; i < 256; i += BLOCK) sh.hist[i] = 0;
-        __syncthreads();
+    __syncthreads();                              // the previous user of sh is done
+    for (int i = tid; i < 4 * 256; i += BLOCK) (&sh.hist[0][0])[i] = 0;
+    __syncthreads();
+    for (int pass = 0; pass < 4; ++pass) {        // two barriers per pass
+        const int shift = 24 - 8 * pass;
+        uint32_t *hist = sh.hist[pass];
         // several independent key reads in flight per thread before their histogram updates
         int64_t i = tid;
         for (; i + 3 * BLOCK < n; i += 4 * BLOCK) {
@@ -33,17 +51,17 @@ __device__ void block_radix_select(KeyFn key, int64_t n, uint32_t nsel, SelectSh
             for (int u = 0; u < 4; ++u) k[u] = key(i + u * BLOCK);
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                if ((k[u] & mask) == prefix) atomicAdd(&sh.hist[(k[u] >> shift) & 255u], 1u);
+                if ((k[u] & mask) == prefix) hist_add(hist, (k[u] >> shift) & 255u);
         }
         for (; i < n; i += BLOCK) {
             uint32_t k = key(i);
-            if ((k & mask) == prefix) atomicAdd(&sh.hist[(k >> shift) & 255u], 1u);
+            if ((k & mask) == prefix) hist_add(hist, (k >> shift) & 255u);
         }
         __syncthreads();
         if (tid < WAVE) {
             uint32_t c[4], s = 0;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { c[j] = sh.hist[4 * tid + j]; s += c[j]; }
+            for (int j = 0; j < 4; ++j) { c[j] = hist[4 * tid + j]; s += c[j]; }
             uint32_t inc = wave_inclusive_scan(s);
             uint32_t exc = inc - s;
             if (exc < remaining && inc >= remaining) {   // exactly one lane
@@ -51,18 +69,17 @@ __device__ void block_radix_select(KeyFn key, int64_t n, uint32_t nsel, SelectSh
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     if (cum < remaining && cum + c[j] >= remaining) {
-                        sh.pick[0] = 4 * tid + j;
-                        sh.pick[1] = remaining - cum;
+                        sh.pick[pass][0] = 4 * tid + j;
+                        sh.pick[pass][1] = remaining - cum;
                     }
                     cum += c[j];
                 }
             }
         }
         __syncthreads();
-        prefix |= sh.pick[0] << shift;
+        prefix |= sh.pick[pass][0] << shift;
         mask |= 0xFFu << shift;
-        remaining = sh.pick[1];
-        __syncthreads();
+        remaining = sh.pick[pass][1];
     }
     pivot = prefix;
     need = remaining;
