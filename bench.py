@@ -166,7 +166,9 @@ def main():
                    "index_build": mode, **{k_: v for k_, v in stats.items()}},
         "codes_scanned_per_s": codes_scanned * args.steps / (stage_ms["scan"] * 1e-3) if stage_ms["scan"] > 0 else 0.0,
         "stage_ms_per_step": {k_: v / args.steps for k_, v in stage_ms.items()},
-        "coarse_gemm_tflops": coarse_tflops,
+        "coarse_gemm_tflops": coarse_tflops,     # useful 2*nq*K*D flop; each is three fp16 matrix-core products
+        "arithmetic": "fp32 results throughout; stage-1 inner products as fp16 hi/lo split operands (22 bits) "
+                      "accumulated in fp32 on the matrix cores, same accuracy as fp32",
         "roofline": {"kernel": "scan_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_SCAN_TRAFFIC_BYTES.get(spec.name),
