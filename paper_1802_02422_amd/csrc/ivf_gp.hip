@@ -156,7 +156,7 @@ int launch_probe_select(const float *Dt, const float *bm, int64_t nq, int64_t K,
 {
     const int nb = (int)((K + BMW - 1) / BMW);
     const size_t lds = (size_t)2 * P * sizeof(int);
-    if (P <= PS_P_MAX && nb <= PS_NB_MAX && nq > 64) {   // keys in LDS (throughput path)
+    if (P <= PS_P_MAX && nb <= PS_NB_MAX) {   // keys in LDS
         const size_t lds2 = ((size_t)2 * P + (nb > 2 * PS_CAP ? nb : 2 * PS_CAP)) * sizeof(int);
         if (lds2 > 48 * 1024)
             HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&probe_select_lds_kernel),
@@ -370,7 +370,7 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
     if ((rc = ensure(ix->partial, (size_t)tile * merge_n * sizeof(uint64_t)))) return rc;
 
     const size_t scan_lds = (size_t)SCAN_WAVES * pool_capacity(k) * sizeof(uint64_t);   // dynamic part: the pools
-    const size_t merge_lds = (size_t)merge_pow2 * sizeof(uint64_t);
+    const size_t merge_lds = ((size_t)merge_n + merge_pow2) * sizeof(uint64_t);
     const size_t sp_lds = (size_t)(PL + 3 * P) * sizeof(uint32_t);
     if (sp_lds > 128 * 1024) return fail(IVF_EINVAL, "nprobe*L=%lld exceeds the 32768 scores one workgroup holds", (long long)PL);
     if (sp_lds > 48 * 1024) {
@@ -378,6 +378,9 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
                                    : reinterpret_cast<const void *>(&score_prune_kernel<256>);
         HIPCHK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sp_lds));
     }
+    if (merge_lds > 40 * 1024)
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&merge_kernel<256>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_lds));
     if (scan_lds > 32 * 1024) {   // dynamic + static LDS above the default 64 KB window
         const void *fn = M == 16 ? reinterpret_cast<const void *>(&scan_kernel<16>)
                                  : reinterpret_cast<const void *>(&scan_kernel<8>);

@@ -380,26 +380,52 @@ __global__ __launch_bounds__(SCAN_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4
     for (int i = lane; i < k; i += WAVE) out[i] = i < pool_n ? pool[i] : EMPTY_KEY;
 }
 
-// Final k-select: replace the position of every partial key by the point's id,
-// sort the n_lists * k keys (distance, id) of a query and write the k best;
-// empty slots become (-1, +inf).
+// Final k-select: replace the position of every partial key by the point's id and write the k
+// best of a query's n_in keys by (distance, id); empty slots become (-1, +inf).  Two steps: a
+// radix select on the distance word finds the k-th smallest distance, then only the keys at or
+// below it (k of them, plus ties on that distance) are sorted, instead of all n_in.
+// Dynamic LDS: (n_in + n_pow2) keys, n_pow2 = next power of two of n_in.
 template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void merge_kernel(const uint64_t *__restrict__ partial,
                                                       const int32_t *__restrict__ ids, int n_in,
                                                       int n_pow2, int k, int32_t *__restrict__ out_ids,
                                                       float *__restrict__ out_dists)
 {
+    __shared__ SelectShared sh;
+    __shared__ uint32_t cnt_s;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint64_t *a = reinterpret_cast<uint64_t *>(smem);
+    uint64_t *a = reinterpret_cast<uint64_t *>(smem);      // n_in gathered keys
+    uint64_t *b = a + n_in;                                // the selected ones, sorted
     const int64_t q = blockIdx.x;
-    for (int i = threadIdx.x; i < n_pow2; i += BLOCK) {
-        uint64_t key = i < n_in ? partial[q * n_in + i] : EMPTY_KEY;
-        if (key != EMPTY_KEY) key = (key & 0xFFFFFFFF00000000ull) | (uint32_t)ids[(uint32_t)key];
+    uint32_t have = 0;
+    for (int i = threadIdx.x; i < n_in; i += BLOCK) {
+        uint64_t key = partial[q * n_in + i];
+        if (key != EMPTY_KEY) {
+            key = (key & 0xFFFFFFFF00000000ull) | (uint32_t)ids[(uint32_t)key];
+            ++have;
+        }
         a[i] = key;
     }
-    block_bitonic_sort<BLOCK>(a, n_pow2);
+    uint32_t n_valid;
+    block_exclusive_scan<BLOCK>(have, sh.scan, n_valid);   // contains barriers: a[] is complete
+    uint32_t pivot = 0xFFFFFFFFu, need = 0;
+    auto hi = [a](int64_t i) { return (uint32_t)(a[i] >> 32); };
+    if (n_valid > (uint32_t)k) block_radix_select<BLOCK>(hi, n_in, (uint32_t)k, sh, pivot, need);   // uniform branch
+    // keys with distance <= pivot, in any order (ties on the pivot distance are all kept: the sort decides by id)
+    if (threadIdx.x == 0) cnt_s = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < n_in; i += BLOCK) {
+        const uint64_t key = a[i];
+        if (key != EMPTY_KEY && (uint32_t)(key >> 32) <= pivot) b[atomicAdd(&cnt_s, 1u)] = key;
+    }
+    __syncthreads();
+    const int m = (int)cnt_s;
+    int mp = 1;
+    while (mp < m) mp <<= 1;
+    for (int i = m + threadIdx.x; i < mp; i += BLOCK) b[i] = EMPTY_KEY;
+    block_bitonic_sort<BLOCK>(b, mp);
     for (int i = threadIdx.x; i < k; i += BLOCK) {
-        uint64_t key = i < n_pow2 ? a[i] : EMPTY_KEY;
+        uint64_t key = i < m ? b[i] : EMPTY_KEY;
         bool empty = key == EMPTY_KEY;
         out_ids[q * k + i] = empty ? -1 : (int32_t)(uint32_t)key;
         out_dists[q * k + i] = empty ? INFINITY : key_float((uint32_t)(key >> 32));
