@@ -720,7 +720,7 @@ __global__ __launch_bounds__(BLOCK) void probe_select_kernel(const float *__rest
 // smallest block minimum, so the P closest centroids are among them; with randomly numbered
 // centroids little more than P survive), compacted in ascending centroid id, and selected
 // from LDS.  A query with more than PS_CAP survivors (duplicated centroids) takes the
-// global-memory path of probe_select_kernel.  Dynamic LDS: 2P + max(nb, 2 PS_CAP) words.
+// global-memory path of probe_select_kernel.  Dynamic LDS: 2P + 3 + max(nb, 2 PS_CAP) words.
 constexpr int PS_NB_MAX = 16384, PS_P_MAX = 256, PS_CAP = 4096, PS_IPT = 2 * PS_P_MAX * BMW / 1024;
 
 __global__ __launch_bounds__(1024) void probe_select_lds_kernel(const float *__restrict__ Dt, int64_t ldt,
@@ -734,7 +734,7 @@ __global__ __launch_bounds__(1024) void probe_select_lds_kernel(const float *__r
     __shared__ uint32_t nflag_s;
     extern __shared__ __attribute__((aligned(16))) int ps_dyn[];
     int *blist = ps_dyn;                                           // 2P flagged blocks
-    uint32_t *keys = reinterpret_cast<uint32_t *>(ps_dyn + 2 * P); // nb block-minimum keys, then the survivors
+    uint32_t *keys = reinterpret_cast<uint32_t *>(ps_dyn + ((2 * P + 3) & ~3));   // (16-byte aligned) nb block-minimum keys, then the survivors
     const int tid = threadIdx.x;
     const int64_t q = blockIdx.x;
     const float *row = Dt + q * ldt;
@@ -745,7 +745,7 @@ __global__ __launch_bounds__(1024) void probe_select_lds_kernel(const float *__r
     const uint32_t nselb = P < nb ? (uint32_t)P : (uint32_t)nb;
     uint32_t t, needb;
     block_radix_select<BLOCK>(keyb, nb, nselb, sh, t, needb);
-    uint32_t nflag = block_emit_selected_runs<BLOCK>(keyb, nb, t, (uint32_t)P, sh,
+    uint32_t nflag = block_emit_selected_runs<BLOCK>(keys, nb, t, (uint32_t)P, sh,
                                                      [&](uint32_t pos, int64_t b, uint32_t) { blist[pos] = (int)b; });
     if (tid == 0) nflag_s = nflag;
     __syncthreads();                                               // blist complete, the block keys are dead
@@ -801,7 +801,7 @@ __global__ __launch_bounds__(1024) void probe_select_lds_kernel(const float *__r
     auto skey = [sk](int64_t i) { return sk[i]; };
     uint32_t pivot, need;
     block_radix_select<BLOCK>(skey, (int64_t)total, (uint32_t)P, sh, pivot, need);
-    block_emit_selected_runs<BLOCK>(skey, (int)total, pivot, need, sh,
+    block_emit_selected_runs<BLOCK>(sk, (int)total, pivot, need, sh,
                                     [&](uint32_t pos, int64_t i, uint32_t k) {
                                         probe_id[q * P + pos] = si[i];
                                         probe_d[q * P + pos] = key_float(k);

@@ -157,7 +157,7 @@ int launch_probe_select(const float *Dt, const float *bm, int64_t nq, int64_t K,
     const int nb = (int)((K + BMW - 1) / BMW);
     const size_t lds = (size_t)2 * P * sizeof(int);
     if (P <= PS_P_MAX && nb <= PS_NB_MAX) {   // keys in LDS
-        const size_t lds2 = ((size_t)2 * P + (nb > 2 * PS_CAP ? nb : 2 * PS_CAP)) * sizeof(int);
+        const size_t lds2 = ((size_t)2 * P + 3 + (nb > 2 * PS_CAP ? nb : 2 * PS_CAP)) * sizeof(int);
         if (lds2 > 48 * 1024)
             HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&probe_select_lds_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2));

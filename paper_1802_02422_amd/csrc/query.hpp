@@ -61,7 +61,7 @@ __global__ __launch_bounds__(BLOCK) void score_prune_kernel(
     uint32_t pivot, need;
     block_radix_select<BLOCK>(key, PL, (uint32_t)S, sh, pivot, need);
     unsigned long long mine = 0;
-    block_emit_selected_runs<BLOCK>(key, PL, pivot, need, sh,
+    block_emit_selected_runs<BLOCK>(keys, PL, pivot, need, sh,
                                [&](uint32_t pos, int64_t i, uint32_t k) {
                                    const int64_t b = (int64_t)pid[i / L] * L + (i % L);
                                    const uint4 info = sub_info[b];   // one 16-byte read per kept subregion

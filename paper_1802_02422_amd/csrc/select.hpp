@@ -115,32 +115,45 @@ __device__ uint32_t block_emit_selected(KeyFn key, int64_t n, uint32_t nsel, uin
     return run_lt + (run_eq < need ? run_eq : need);
 }
 
-// The same selection for keys that are cheap to re-read (LDS): every thread owns a contiguous
-// run of ceil(n / BLOCK) items, counts its selected ones, one workgroup scan turns the counts
-// into output offsets, and the thread then emits its run in order.  One scan instead of one
-// per BLOCK items.  n < 65536.
-template <int BLOCK, class KeyFn, class EmitFn>
-__device__ uint32_t block_emit_selected_runs(KeyFn key, int n, uint32_t pivot, uint32_t need,
+// The same selection for keys held in LDS (16-byte aligned, readable up to the next multiple of
+// four past n): every thread owns a contiguous run of items, reads it once with 128-bit loads
+// into registers (a run per thread read word by word would put 16 lanes on every bank), counts
+// its selected items, one workgroup scan turns the counts into output offsets, and the thread
+// emits its run in order.  One scan instead of one per BLOCK items.  n <= 32 * BLOCK, n < 65536.
+template <int BLOCK, class EmitFn>
+__device__ uint32_t block_emit_selected_runs(const uint32_t *keys, int n, uint32_t pivot, uint32_t need,
                                              SelectShared &sh, EmitFn emit)
 {
-    const int ipt = (n + BLOCK - 1) / BLOCK;
-    const int i0 = threadIdx.x * ipt, i1 = i0 + ipt < n ? i0 + ipt : n;
+    constexpr int MAXV = 8;                                   // 128-bit words per thread
+    const int ipt = ((n + BLOCK - 1) / BLOCK + 3) & ~3;       // items per thread, a multiple of 4
+    const int i0 = threadIdx.x * ipt;
+    uint32_t kv[4 * MAXV];
     uint32_t lt = 0, eq = 0;
-    for (int i = i0; i < i1; ++i) {
-        const uint32_t k = key(i);
-        lt += k < pivot;
-        eq += k == pivot;
+#pragma unroll
+    for (int v = 0; v < MAXV; ++v) {
+        uint4 w = make_uint4(0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu);
+        if (4 * v < ipt && i0 + 4 * v < n) w = *reinterpret_cast<const uint4 *>(&keys[i0 + 4 * v]);
+        kv[4 * v + 0] = w.x; kv[4 * v + 1] = w.y; kv[4 * v + 2] = w.z; kv[4 * v + 3] = w.w;
+    }
+    bool in[4 * MAXV];
+#pragma unroll
+    for (int j = 0; j < 4 * MAXV; ++j) {
+        in[j] = j < ipt && i0 + j < n;
+        lt += (in[j] && kv[j] < pivot) ? 1u : 0u;
+        eq += (in[j] && kv[j] == pivot) ? 1u : 0u;
     }
     uint32_t total;
     const uint32_t exc = block_exclusive_scan<BLOCK>(lt | (eq << 16), sh.scan, total);
     uint32_t lt_seen = exc & 0xFFFFu, eq_seen = exc >> 16;
-    for (int i = i0; i < i1; ++i) {
-        const uint32_t k = key(i);
+#pragma unroll
+    for (int j = 0; j < 4 * MAXV; ++j) {
+        if (!in[j]) continue;
+        const uint32_t k = kv[j];
         if (k < pivot) {
-            emit(lt_seen + (eq_seen < need ? eq_seen : need), (int64_t)i, k);
+            emit(lt_seen + (eq_seen < need ? eq_seen : need), (int64_t)(i0 + j), k);
             ++lt_seen;
         } else if (k == pivot) {
-            if (eq_seen < need) emit(lt_seen + eq_seen, (int64_t)i, k);
+            if (eq_seen < need) emit(lt_seen + eq_seen, (int64_t)(i0 + j), k);
             ++eq_seen;
         }
     }
