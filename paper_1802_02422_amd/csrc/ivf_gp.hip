@@ -343,6 +343,7 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
     int64_t tile = ix->scratch_limit / (K * (int64_t)sizeof(float));
     if (tile < 1) tile = 1;
     if (tile >= nq) tile = nq;
+    else if (tile >= 256) tile -= tile % 256;   // whole blocks of the padded row count
     else if (tile >= GT) tile -= tile % GT;
 
     // workgroups per query in the scan: fill the chip when the batch is small
@@ -499,6 +500,7 @@ extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const f
     int64_t tile = (4ll << 30) / (K * (int64_t)sizeof(float));
     if (tile < 1) tile = 1;
     if (tile >= nq) tile = nq;
+    else if (tile >= 256) tile -= tile % 256;   // whole blocks of the padded row count
     else if (tile >= GT) tile -= tile % GT;
     float *cn = nullptr, *xn = nullptr, *Dt = nullptr, *bm = nullptr, *csi = nullptr, *xsi = nullptr;
     _Float16 *cpk = nullptr, *xpk = nullptr;
