@@ -368,7 +368,9 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) |
 // Waiting for a copy with operations issued after it still in flight relies on in-order
 // completion; the counts below are the vector-memory operations a wavefront issues between a
 // copy and the step that consumes it, or a lower bound of them (2 copies a step, at least 16
-// stores an epilogue).  Only whole tiles are handled (nq a multiple of 128 here, K a multiple
+// stores an epilogue).  With six stages the ring holds a whole tile and every copy is issued
+// ahead of the stores of the tile before the one it belongs to: a wavefront never has to wait
+// for its stores to drain before it can go on, it runs up to one tile ahead of them.  Only whole tiles are handled (nq a multiple of 128 here, K a multiple
 // of 128): the host gives the last, partial query tile to coarse_gemm_kernel.  The workgroup barrier of a step orders LDS traffic only (operands arrive by copies
 // that each wavefront has waited for, nothing else is shared), so it is issued without the
 // global-memory fence of __syncthreads, which would drain the queue at every step.
@@ -442,8 +444,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             __builtin_amdgcn_global_load_lds((gptr_t)(src + (int64_t)n * 16 * Dp), (lptr_t)(dst + n * 256), 16, 0, 0);
     };
 
+    // RING == STAGES: the ring holds one whole tile; the copy of a stage of the next tile is issued
+    // one step after that stage was consumed, and the last one right after the tile's MFMA work,
+    // ahead of the epilogue's stores, so that no copy ever queues behind a store it is needed before.
+    constexpr bool WHOLE = RING == STAGES;
 #pragma unroll
-    for (int s = 0; s < PD; ++s) issue(t_begin, s);
+    for (int s = 0; s < (WHOLE ? STAGES : PD); ++s) issue(t_begin, s);
 
     // query fragments: for stage s and block i the 32 bytes [hi | lo] of row wq + 32 i + l32, half h
     gu32x4 afr[STAGES][2][2];
@@ -477,9 +483,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     float *stage = stage_all + wave * (16 * SLD);
 
+    float cn_next = 0.f;
     for (int t = t_begin; t < t_end; ++t) {
         const int64_t c0 = (int64_t)(tb + t * IL) * GT;
-        float cn_next = 0.f;
 #pragma unroll
         for (int s = 0; s < STAGES; ++s) {
             // operations issued after the copy of this stage: the copies of the PD - 1 stages after it,
@@ -487,30 +493,51 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             // (the tile's one norm load is left out of the count: wherever the compiler places it,
             // waiting for one operation more than needed is harmless)
             constexpr int COPIES = 2 * (PD - 1);
-            if (s < PD) __builtin_amdgcn_s_waitcnt(vmcnt_imm(COPIES + EPI_STORES));
+            if (WHOLE) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * STAGES - 2 + EPI_STORES));   // the same count at every step
+            else if (s < PD) __builtin_amdgcn_s_waitcnt(vmcnt_imm(COPIES + EPI_STORES));
             else __builtin_amdgcn_s_waitcnt(vmcnt_imm(COPIES));
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            issue(t, s + PD);
-            // norms of the next tile, parked in a register until the middle of this one (an
-            // unconditional load with a clamped index: nothing forces the wave to wait for it here)
-            const int64_t cnx = c0 + (int64_t)IL * GT + (tid & (GT - 1));
-            if (s == 0) cn_next = cn[cnx < K ? cnx : K - 1];
-            if (s == STAGES / 2) cns[(t + 1) & 1][tid & (GT - 1)] = cnx < K ? cn_next : 0.f;
-            const float *Bs = slot_of(s);
+            if (!WHOLE) issue(t, s + PD);
+            else if (s >= 1) issue(t, STAGES + s - 1);
+            // this tile's centroid norms, requested at the end of the previous tile (below), go to LDS
+            // in the middle of this one: the stores of the previous epilogue and the copies of the
+            // steps since were issued after that load
+            if (s == STAGES / 2 && t > t_begin) {
+                asm volatile("s_waitcnt vmcnt(%1)" : "+v"(cn_next) : "n"(EPI_STORES + 2 * (STAGES / 2)));
+                cns[t & 1][tid & (GT - 1)] = cn_next;
+            }
+            // The centroid fragments are read with explicit instructions: for an ordinary LDS read of a
+            // buffer that copies write, the compiler waits for every outstanding vector-memory
+            // operation (the stores of the previous epilogue included).  The waits above and the
+            // barrier already order these reads after the copy they need.
+            const uint32_t bs = (uint32_t)reinterpret_cast<uintptr_t>(slot_of(s));   // LDS byte address
             gu32x4 b[2][2];
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int rb = wc + j * 32 + l32;
 #pragma unroll
-                for (int p = 0; p < 2; ++p)
-                    b[j][p] = *reinterpret_cast<const gu32x4 *>(&Bs[rb * ROWF + (((2 * h + p) ^ ((rb >> 2) & 3)) << 2)]);
+                for (int p = 0; p < 2; ++p) {
+                    const uint32_t at = bs + 4u * (uint32_t)(rb * ROWF + (((2 * h + p) ^ ((rb >> 2) & 3)) << 2));
+                    asm volatile("ds_read_b128 %0, %1" : "=v"(b[j][p]) : "v"(at));
+                }
             }
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[1][0]), "+v"(b[1][1]));
 #pragma unroll
             for (int e = 0; e < 3; ++e)
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int j = 0; j < 2; ++j) acc[i][j] = mfma3(b[j], afr[s][i], acc[i][j], e);
+        }
+        if (WHOLE) {   // everyone is done with the last buffer: refill it before the stores go out
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            issue(t, 2 * STAGES - 1);
+        }
+        {   // norms of the next tile (index clamped past the end).  The load is hidden from the compiler,
+            // which would otherwise drain the whole queue, stores included, where the value is used.
+            const int64_t cnx = c0 + (int64_t)IL * GT + (tid & (GT - 1));
+            const float *pn = cn + (cnx < K ? cnx : K - 1);
+            asm volatile("global_load_dword %0, %1, off" : "=v"(cn_next) : "v"(pn) : "memory");
         }
         const float *cnw = cns[t & 1] + wc;
 #pragma unroll
