@@ -93,6 +93,13 @@ def full_size_case(name, n_sample, extra_batches=()):
     ivf.ivf_set_scratch_limit(handle, 48 << 30)              # the launch configuration bench.py times
     out = ivf.ivf_search_stages(handle, Q, spec.nprobe, spec.prune_frac, spec.k)
     torch.cuda.synchronize()
+    # every query, not only the sampled ones: a second run of the whole batch returns the same bits
+    # (the kernels' hand-counted waits on asynchronous copies would show up here as run-to-run noise)
+    again = ivf.ivf_search_stages(handle, Q, spec.nprobe, spec.prune_frac, spec.k)
+    torch.cuda.synchronize()
+    for n in ("probe_id", "probe_d", "kept_sub", "ids", "dists"):
+        assert torch.equal(out[n], again[n]), (name, n)
+    del again
     sample = np.linspace(0, spec.nq - 1, n_sample).astype(np.int64)
     out = {n: v[torch.from_numpy(sample).to(dev)].cpu().numpy() for n, v in out.items()}
     rep = parity.check_search(ix, Q.cpu().numpy()[sample], spec.nprobe, spec.prune_frac, spec.k, out)
