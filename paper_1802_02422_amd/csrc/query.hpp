@@ -8,7 +8,7 @@ namespace ivf {
 
 // One kept subregion of one query, as the scan consumes it.
 struct SubDesc {
-    uint32_t blk;    // start of the subregion's record block, in 64-byte units
+    uint32_t blk;    // start of the subregion's record block, in BLK_ALIGN-byte units
     uint32_t pos0;   // grouped position of its first point (indexes ids[])
     uint32_t len;    // number of points
     float base;      // distance from the query to the subcentroid

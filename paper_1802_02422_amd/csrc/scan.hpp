@@ -1,10 +1,11 @@
 // Stages 5-6: the asymmetric-distance scan of the kept subregions with
 // per-wavefront top-k pools (Eq. (6)), and the final k-select.
 //
-// Record layout (built at load time): subregion b owns a 64-byte aligned block
-// at byte offset 64*blk_off[b] holding len*M code bytes followed by len
+// Record layout (built at load time): subregion b owns a 16-byte aligned block
+// at byte offset BLK_ALIGN*blk_off[b] holding len*M code bytes followed by len
 // constant-term bytes, so one subregion is one contiguous HBM run.
 #pragma once
+#include "layout.hpp"
 #include "query.hpp"
 
 namespace ivf {
@@ -305,7 +306,7 @@ __global__ __launch_bounds__(SCAN_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4
         t_next = 0;
         carry = 0;
         wave_sync();
-        const uint64_t pc = reinterpret_cast<uint64_t>(blocks) + (uint64_t)sd.x * 64u;
+        const uint64_t pc = reinterpret_cast<uint64_t>(blocks) + (uint64_t)sd.x * (uint64_t)BLK_ALIGN;
         const uint64_t pb = pc + (uint64_t)len * M;
         const uint64_t ne = __ballot(len > 0);
         const uint32_t slot = __builtin_amdgcn_mbcnt_hi((uint32_t)(ne >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ne, 0u));
