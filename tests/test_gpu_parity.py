@@ -74,6 +74,32 @@ def test_coarse_distances_within_fp32_bound_for_all_kernel_variants(D, K, nq):
         assert np.isin(must, gid[q]).all()
 
 
+def test_coarse_topk_beyond_the_lds_selection_limits():
+    """More than 2^20 centroids (block minima no longer fit LDS) and more than 256 probes: the
+    global-memory selection kernels, checked against brute force."""
+    print("case: coarse_topk K = 1 100 003", flush=True)
+    rng = np.random.default_rng(77)
+    K, D = 1_100_003, 32
+    C = rng.standard_normal((K, D)).astype(np.float32)
+    Q = rng.standard_normal((70, D)).astype(np.float32)
+    Cg = torch.from_numpy(C).cuda()
+    c64 = C.astype(np.float64)
+    cn = (c64 ** 2).sum(1)
+    u = 2.0 ** -24
+    for nq, P in ((3, 16), (70, 300)):
+        gid, gd = ivf.ivf_coarse_topk(Cg, torch.from_numpy(Q[:nq]).cuda(), P)
+        gid, gd = gid.cpu().numpy(), gd.cpu().numpy()
+        for q in range(nq):
+            q64 = Q[q].astype(np.float64)
+            exact = np.maximum((q64 ** 2).sum() + cn - 2.0 * (c64 @ q64), 0.0)
+            tol = 16 * u * ((q64 ** 2).sum() + cn.max())
+            kth = np.partition(exact, P - 1)[P - 1]
+            assert len(set(gid[q].tolist())) == P and (np.diff(gid[q]) > 0).all()
+            assert (np.abs(gd[q] - exact[gid[q]]) <= tol).all()
+            assert (exact[gid[q]] <= kth + 2 * tol).all()
+            assert np.isin(np.nonzero(exact < kth - 2 * tol)[0], gid[q]).all()
+
+
 def test_search_tiny_all_stages(tiny_gpu):
     spec, ix, Q, X, handle = tiny_gpu
     print("case: search tiny", spec, flush=True)
