@@ -181,14 +181,14 @@ int ivf_alpha_stats(const float *centroids, int64_t K, int D, const int32_t *nbr
 /*
  * Per-stage device timing of ivf_search / ivf_search_stages on a handle.  While
  * enabled, every pass over a tile of queries records HIP events on the caller's
- * stream around its seven kernel groups, in launch order:
- *   0 query norms + coarse distance GEMM   1 nprobe selection   2 Eq. (7) scoring fused with
- *   the pruning select   3 (empty)   4 lookup tables   5 ADC scan   6 final k-select
+ * stream around its six kernel groups, in launch order:
+ *   0 query packing + coarse distance GEMM   1 nprobe selection   2 Eq. (7) scoring fused with
+ *   the pruning select   3 lookup tables   4 ADC scan   5 final k-select
  * ivf_profile_read waits for the device, writes the summed milliseconds per
  * group to stage_ms[IVF_N_STAGES] (host) and the number of passes to *launches
  * (host), and resets the counters.
  */
-#define IVF_N_STAGES 7
+#define IVF_N_STAGES 6
 int ivf_profile_enable(ivf_index *index, int on);
 int ivf_profile_read(ivf_index *index, double *stage_ms, int64_t *launches);
 

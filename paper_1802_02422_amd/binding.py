@@ -255,7 +255,7 @@ def ivf_alpha_stats(centroids: torch.Tensor, nbr: torch.Tensor, x: torch.Tensor,
                                           _ptr(num), _ptr(den), _stream()))
 
 
-STAGE_NAMES = ("coarse_gemm", "probe_select", "score_prune", "unused", "lut", "scan", "merge")
+STAGE_NAMES = ("coarse_gemm", "probe_select", "score_prune", "lut", "scan", "merge")
 
 
 def ivf_profile_enable(index: IndexHandle, on: bool) -> None:

@@ -427,11 +427,10 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
                 Dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, desc, ks, ns);
         LAUNCHCHK("score_prune_kernel");
         if ((rc = mark(3))) return rc;
-        if ((rc = mark(4))) return rc;
 
         lut_kernel<<<dim3((unsigned)n), dim3(256), (size_t)D * sizeof(float), st>>>(Q, D, M, ix->codebook, lut);
         LAUNCHCHK("lut_kernel");
-        if ((rc = mark(5))) return rc;
+        if ((rc = mark(4))) return rc;
 
         if (M == 16)
             scan_kernel<16><<<dim3((unsigned)(n * nsplit)), dim3(SCAN_BLOCK), scan_lds, st>>>(
@@ -440,12 +439,12 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
             scan_kernel<8><<<dim3((unsigned)(n * nsplit)), dim3(SCAN_BLOCK), scan_lds, st>>>(
                 ix->blocks, ix->const_table, desc, S, lut, k, nsplit, partial);
         LAUNCHCHK("scan_kernel");
-        if ((rc = mark(6))) return rc;
+        if ((rc = mark(5))) return rc;
 
         merge_kernel<256><<<dim3((unsigned)n), dim3(256), merge_lds, st>>>(
             partial, ix->ids, merge_n, merge_pow2, k, out_ids + q0 * k, out_dists + q0 * k);
         LAUNCHCHK("merge_kernel");
-        if ((rc = mark(7))) return rc;
+        if ((rc = mark(6))) return rc;
         if (ix->profile) ix->launches++;
     }
     return IVF_OK;

@@ -22,12 +22,6 @@ __device__ __forceinline__ float key_float(uint32_t k)
     return __uint_as_float(u);
 }
 
-// (distance, id) packed so that integer order is (distance, id) order
-__device__ __forceinline__ uint64_t dist_id_key(float d, int32_t id)
-{
-    return ((uint64_t)float_key(d) << 32) | (uint32_t)id;
-}
-
 // LDS traffic between lanes of one wavefront: keep the compiler from moving
 // LDS accesses across this point (the hardware executes a wave's LDS
 // instructions in order).
@@ -46,30 +40,8 @@ __device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v)
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
 }
 
-// DPP move of a float; lanes without a source (row excluded by ROW_MASK) get `fill`.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_float(float v, float fill = 0.f)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(fill), __float_as_int(v), CTRL,
-                                                      ROW_MASK, 0xf, false));
-}
-
-// Inclusive running maximum over the 64 lanes in 6 DPP steps, no LDS:
-// row_shr 1/2/4/8 scan each row of 16, row_bcast15 carries rows 0,2 into rows
-// 1,3, row_bcast31 carries lane 31 into rows 2,3.
-__device__ __forceinline__ uint32_t wave_inclusive_max_scan(uint32_t v)
-{
-    uint32_t t;
-    t = dpp_or_zero<0x111, 0xf>(v); v = t > v ? t : v;
-    t = dpp_or_zero<0x112, 0xf>(v); v = t > v ? t : v;
-    t = dpp_or_zero<0x114, 0xf>(v); v = t > v ? t : v;
-    t = dpp_or_zero<0x118, 0xf>(v); v = t > v ? t : v;
-    t = dpp_or_zero<0x142, 0xa>(v); v = t > v ? t : v;
-    t = dpp_or_zero<0x143, 0xc>(v); v = t > v ? t : v;
-    return v;
-}
-
-// Inclusive prefix sum over the 64 lanes, the same six DPP steps.
+// Inclusive prefix sum over the 64 lanes in 6 DPP steps, no LDS: row_shr 1/2/4/8 scan each row
+// of 16, row_bcast15 carries rows 0,2 into rows 1,3, row_bcast31 carries lane 31 into rows 2,3.
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
 {
     v += dpp_or_zero<0x111, 0xf>(v);
