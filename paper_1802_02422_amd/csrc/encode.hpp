@@ -6,14 +6,15 @@
 
 namespace ivf {
 
-// LDS per workgroup (one wavefront): x, c and e/mu, each D floats.
+// LDS per workgroup (one wavefront): x, c and e/mu, each D floats.  With codebook == NULL the
+// kernel stops after the displacement (written to out_res, the subcentroid to out_mu).
 __global__ __launch_bounds__(64) void encode_kernel(
     const float *__restrict__ X, int64_t n, int D, int M, int L, const int32_t *__restrict__ region,
     const float *__restrict__ C, const int32_t *__restrict__ nbr, const float *__restrict__ alpha,
     const float *__restrict__ cs_dist2, const float *__restrict__ codebook,
     const float *__restrict__ const_table, int32_t *__restrict__ out_sub,
     uint8_t *__restrict__ out_codes, uint8_t *__restrict__ out_byte, float *__restrict__ out_t,
-    float *__restrict__ out_res)
+    float *__restrict__ out_res, float *__restrict__ out_mu)
 {
     extern __shared__ float sm[];
     float *xs = sm, *cs = sm + D, *es = sm + 2 * D, *mus = sm + 3 * D;
@@ -61,9 +62,10 @@ __global__ __launch_bounds__(64) void encode_kernel(
         mus[t] = mu;
         es[t] = xs[t] - mu;
         if (out_res) out_res[i * D + t] = xs[t] - mu;
+        if (out_mu) out_mu[i * D + t] = mu;
     }
     wave_sync();
-    if (!codebook) return;   // trained up to alpha only: region / subregion / displacement
+    if (!codebook) return;   // trained up to alpha only, or the codes are left to pq_encode_kernel
 
     // PQ: nearest of the 256 codewords per block of D/M dims, lowest index on ties
     const int ds = D / M;
@@ -100,6 +102,65 @@ __global__ __launch_bounds__(64) void encode_kernel(
         }
         wave_argmin(bd, bj);
         if (lane == 0) out_byte[i] = (uint8_t)bj;
+    }
+}
+
+// PQ encoding of displacements, one THREAD per point with the whole codebook in LDS (M * 256 * DS
+// floats, DS = D / M): all lanes walk the 256 codewords of a block together, so every codeword
+// is one broadcast LDS read, the running minimum stays in the lane (no cross-lane reduction), and
+// the arithmetic per (point, codeword) is the same sequence of fused multiply-adds as in
+// encode_kernel: the codes are identical.  Also the per-point constant t = 2<mu, r> + ||r||^2
+// of Eq. (6) and its nearest table entry, lowest index on ties.  E and MU are [n][D] fp32.
+// A workgroup encodes several batches of blockDim.x points (grid-stride).
+template <int DS>
+__global__ __launch_bounds__(1024) void pq_encode_kernel(
+    const float *__restrict__ E, const float *__restrict__ MU, int64_t n, int M,
+    const float *__restrict__ codebook, const float *__restrict__ const_table,
+    uint8_t *__restrict__ out_codes, uint8_t *__restrict__ out_byte, float *__restrict__ out_t)
+{
+    extern __shared__ __attribute__((aligned(16))) float cb[];   // M * 256 * DS
+    __shared__ float tab[256];
+    const int D = M * DS;
+    for (int i = threadIdx.x; i < M * 256 * DS; i += blockDim.x) cb[i] = codebook[i];
+    if (threadIdx.x < 256) tab[threadIdx.x] = const_table ? const_table[threadIdx.x] : 0.f;
+    __syncthreads();
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        float tval = 0.f;
+        for (int m = 0; m < M; ++m) {
+            float ev[DS];
+#pragma unroll
+            for (int t = 0; t < DS; ++t) ev[t] = E[i * D + m * DS + t];
+            float bd = INFINITY;
+            int bj = 0;
+            const float *cwm = cb + m * 256 * DS;
+#pragma unroll 4
+            for (int j = 0; j < 256; ++j) {
+                float dd = 0.f;
+#pragma unroll
+                for (int t = 0; t < DS; ++t) {
+                    const float u = ev[t] - cwm[j * DS + t];
+                    dd = fmaf(u, u, dd);
+                }
+                if (dd < bd) { bd = dd; bj = j; }   // ascending j: lowest index on ties
+            }
+            out_codes[i * M + m] = (uint8_t)bj;
+            const float *cw = cwm + bj * DS;
+#pragma unroll
+            for (int t = 0; t < DS; ++t) {
+                const float rv = cw[t];
+                tval = fmaf(2.f * MU[i * D + m * DS + t], rv, fmaf(rv, rv, tval));
+            }
+        }
+        if (out_t) out_t[i] = tval;
+        if (const_table) {
+            float bd = INFINITY;
+            int bj = 0;
+            for (int j = 0; j < 256; ++j) {
+                const float dd = fabsf(tval - tab[j]);
+                if (dd < bd) { bd = dd; bj = j; }
+            }
+            out_byte[i] = (uint8_t)bj;
+        }
     }
 }
 

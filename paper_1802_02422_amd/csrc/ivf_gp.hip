@@ -593,12 +593,64 @@ extern "C" int ivf_encode(const ivf_index_desc *t, const float *x, int64_t n, co
         g_err = keep;
         if (rc) return rc;
     }
-    encode_kernel<<<dim3((unsigned)n), dim3(64), (size_t)4 * t->D * sizeof(float), st>>>(
-        x, n, t->D, t->M, t->L, out_region, t->centroids, t->nbr, t->alpha, t->cs_dist2, t->pq_codebook,
-        t->const_table, out_sub, out_codes, out_const_byte, out_const_t, out_residual);
-    LAUNCHCHK("encode_kernel");
-    HIPCHK(hipStreamSynchronize(st));
-    return IVF_OK;
+    // PQ codes by the thread-per-point kernel when the codebook fits LDS and D / M is one of the
+    // compiled block widths; else by the wavefront-per-point kernel, which does everything.
+    const int ds = t->D / t->M;
+    const size_t cb_bytes = (size_t)256 * t->D * sizeof(float);
+    const bool fast = t->pq_codebook && cb_bytes <= 140 * 1024 &&
+                      (ds == 4 || ds == 6 || ds == 8 || ds == 12 || ds == 16);
+    if (!fast) {
+        encode_kernel<<<dim3((unsigned)n), dim3(64), (size_t)4 * t->D * sizeof(float), st>>>(
+            x, n, t->D, t->M, t->L, out_region, t->centroids, t->nbr, t->alpha, t->cs_dist2, t->pq_codebook,
+            t->const_table, out_sub, out_codes, out_const_byte, out_const_t, out_residual, nullptr);
+        LAUNCHCHK("encode_kernel");
+        HIPCHK(hipStreamSynchronize(st));
+        return IVF_OK;
+    }
+    const int64_t chunk = n < (1ll << 20) ? n : (1ll << 20);
+    float *e = nullptr, *mu = nullptr;
+    auto body = [&]() -> int {
+        if (!out_residual) HIPCHK(hipMalloc(reinterpret_cast<void **>(&e), (size_t)chunk * t->D * sizeof(float)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&mu), (size_t)chunk * t->D * sizeof(float)));
+        const void *fn = ds == 4 ? (const void *)&pq_encode_kernel<4> : ds == 6 ? (const void *)&pq_encode_kernel<6>
+                       : ds == 8 ? (const void *)&pq_encode_kernel<8> : ds == 12 ? (const void *)&pq_encode_kernel<12>
+                                                                                 : (const void *)&pq_encode_kernel<16>;
+        HIPCHK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)cb_bytes));
+        for (int64_t i0 = 0; i0 < n; i0 += chunk) {
+            const int64_t m = n - i0 < chunk ? n - i0 : chunk;
+            float *ec = out_residual ? out_residual + i0 * t->D : e;
+            encode_kernel<<<dim3((unsigned)m), dim3(64), (size_t)4 * t->D * sizeof(float), st>>>(
+                x + i0 * t->D, m, t->D, t->M, t->L, out_region + i0, t->centroids, t->nbr, t->alpha, t->cs_dist2,
+                nullptr, nullptr, out_sub + i0, nullptr, nullptr, nullptr, ec, mu);
+            LAUNCHCHK("encode_kernel");
+            int64_t grid = (m + 1023) / 1024;
+            if (grid > 512) grid = 512;
+            uint8_t *oc = out_codes + i0 * t->M;
+            uint8_t *ob = out_const_byte ? out_const_byte + i0 : nullptr;
+            float *ot = out_const_t ? out_const_t + i0 : nullptr;
+#define IVF_PQ_LAUNCH(DSV)                                                                               \
+    pq_encode_kernel<DSV><<<dim3((unsigned)grid), dim3(1024), cb_bytes, st>>>(ec, mu, m, t->M, t->pq_codebook, \
+                                                                               t->const_table, oc, ob, ot)
+            if (ds == 4) IVF_PQ_LAUNCH(4);
+            else if (ds == 6) IVF_PQ_LAUNCH(6);
+            else if (ds == 8) IVF_PQ_LAUNCH(8);
+            else if (ds == 12) IVF_PQ_LAUNCH(12);
+            else IVF_PQ_LAUNCH(16);
+#undef IVF_PQ_LAUNCH
+            LAUNCHCHK("pq_encode_kernel");
+        }
+        HIPCHK(hipStreamSynchronize(st));
+        return IVF_OK;
+    };
+    rc = body();
+    {
+        std::string keep = g_err;
+        (void)hipStreamSynchronize(st);
+        if (e) (void)hipFree(e);
+        if (mu) (void)hipFree(mu);
+        g_err = keep;
+    }
+    return rc;
 }
 
 extern "C" int ivf_alpha_stats(const float *centroids, int64_t K, int D, const int32_t *nbr, int L,
