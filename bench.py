@@ -24,7 +24,7 @@ DESC_BYTES = 16          # one kept-subregion descriptor read by the scan
 # HBM bytes per scan launch from rocprofv3 hardware counters (FETCH_SIZE and WRITE_SIZE, each scaled by what
 # the same counter reads for the library's plain 1 GiB copy kernel: 2.0 and 1.0).  Measured offline with the
 # commands in profiles/scan_kernel_<workload>.md; None where no counter run has been made.
-MEASURED_SCAN_TRAFFIC_BYTES = {"deep1b": (5_227_907 * 2.0 + 31_654 * 1.0) * 1024}
+MEASURED_SCAN_TRAFFIC_BYTES = {"deep1b": (5_049_329 * 2.0 + 31_660 * 1.0) * 1024}
 
 
 def log(msg):
