@@ -766,7 +766,22 @@ __global__ __launch_bounds__(1024) void probe_select_lds_kernel(const float *__r
     const int64_t q = blockIdx.x;
     const float *row = Dt + q * ldt;
     const float *bmr = bm + q * nb;
-    for (int i = tid; i < nb; i += BLOCK) keys[i] = float_key(bmr[i]);
+    if ((nb & 3) == 0) {   // rows of bm are then 16-byte aligned: four loads in flight per thread, 128 bits each
+        const float4 *src = reinterpret_cast<const float4 *>(bmr);
+        for (int i0 = tid; i0 < nb / 4; i0 += 4 * BLOCK) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (i0 + u * BLOCK < nb / 4) v[u] = src[i0 + u * BLOCK];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (i0 + u * BLOCK < nb / 4)
+                    *reinterpret_cast<uint4 *>(&keys[4 * (i0 + u * BLOCK)]) =
+                        make_uint4(float_key(v[u].x), float_key(v[u].y), float_key(v[u].z), float_key(v[u].w));
+        }
+    } else {
+        for (int i = tid; i < nb; i += BLOCK) keys[i] = float_key(bmr[i]);
+    }
     __syncthreads();
     auto keyb = [keys](int64_t b) { return keys[b]; };
     const uint32_t nselb = P < nb ? (uint32_t)P : (uint32_t)nb;
