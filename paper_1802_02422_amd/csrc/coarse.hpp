@@ -16,6 +16,7 @@
 
 namespace ivf {
 
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 typedef uint32_t gu32x4 __attribute__((ext_vector_type(4)));
@@ -229,7 +230,10 @@ constexpr int SLD = 64 + 4;   // row stride (floats) of a wavefront's 32x64 outp
 // (acc[j]: centroids 32j .. 32j+31 of the block): distances max(0, qr + cn + m2 * acc), the
 // block minimum per query into bm, and the distances out through the wavefront's LDS staging
 // area, [query][centroid], so that 16 lanes cover one query row and every store instruction
-// writes four rows of 256 contiguous bytes.  qb / cb: first query / centroid of the block;
+// writes four rows of 256 contiguous bytes, as streaming (non-temporal) stores: the matrix is
+// far larger than the caches and is read back by other kernels only after this one has ended,
+// and on the MI355X the sweep kernel runs 10 % faster with them than with ordinary stores.
+// qb / cb: first query / centroid of the block;
 // cnw: the 64 centroid norms of the block (LDS).  EDGE = false skips all bounds checks (the
 // block lies inside Dt and K is a multiple of 4).
 template <bool EDGE, int SROWS = 32>
@@ -302,7 +306,8 @@ __device__ __forceinline__ void emit_block(const floatx16 (&acc)[2], float qr, f
             float *p = Dt + (qp + sr) * ldt + cb + sc;
 #pragma unroll
             for (int it = 0; it < SROWS / 4; ++it) {
-                *reinterpret_cast<float4 *>(p) = *reinterpret_cast<const float4 *>(&stage[(it * 4 + sr) * SLD + sc]);
+                __builtin_nontemporal_store(*reinterpret_cast<const floatx4 *>(&stage[(it * 4 + sr) * SLD + sc]),
+                                            reinterpret_cast<floatx4 *>(p));
                 p += 4 * ldt;
             }
         }
