@@ -228,6 +228,15 @@ extern "C" int ivf_set_scratch_limit(ivf_index *ix, int64_t bytes)
 
 namespace {
 
+// device memory released when the scope ends, error returns included (the owner synchronizes first)
+struct DevTmp {
+    void *p = nullptr;
+    DevTmp() = default;
+    DevTmp(const DevTmp &) = delete;
+    DevTmp &operator=(const DevTmp &) = delete;
+    ~DevTmp() { if (p) (void)hipFree(p); }
+};
+
 template <class T>
 int dev_copy(T *&dst, const T *src, size_t count, hipStream_t st)
 {
@@ -258,30 +267,27 @@ int load_impl(const ivf_index_desc *d, hipStream_t st, ivf_index *ix)
     cst_kernel<<<dim3((unsigned)((nsub + 255) / 256)), dim3(256), 0, st>>>(ix->alpha, d->cs_dist2, L, nsub, ix->cst);
     LAUNCHCHK("cst_kernel");
 
+    // 64-bit check of the 32-bit block offsets: N*(M+1) bytes plus at most one block of padding each
+    if (((uint64_t)N * (M + 1)) / BLK_ALIGN + (uint64_t)nsub >= (1ull << 32))
+        return fail(IVF_EINVAL, "index too large for 32-bit block offsets");
     // block offsets: exclusive prefix sum of the block sizes
-    uint32_t *sz = nullptr;
-    HIPCHK(hipMalloc(reinterpret_cast<void **>(&sz), (size_t)nsub * sizeof(uint32_t)));
-    uint32_t *blk_off = nullptr;
-    HIPCHK(hipMalloc(reinterpret_cast<void **>(&blk_off), (size_t)nsub * sizeof(uint32_t)));
+    DevTmp sz_mem, off_mem, scan_mem;
+    HIPCHK(hipMalloc(&sz_mem.p, (size_t)nsub * sizeof(uint32_t)));
+    HIPCHK(hipMalloc(&off_mem.p, (size_t)nsub * sizeof(uint32_t)));
+    uint32_t *sz = static_cast<uint32_t *>(sz_mem.p), *blk_off = static_cast<uint32_t *>(off_mem.p);
     blk_size_kernel<<<dim3((unsigned)((nsub + 255) / 256)), dim3(256), 0, st>>>(d->sub_offsets, nsub, M, sz);
     LAUNCHCHK("blk_size_kernel");
     size_t tmp_bytes = 0;
     HIPCHK(rocprim::exclusive_scan(nullptr, tmp_bytes, sz, blk_off, 0u, (size_t)nsub,
                                    rocprim::plus<uint32_t>(), st));
-    void *tmp = nullptr;
-    HIPCHK(hipMalloc(&tmp, tmp_bytes ? tmp_bytes : 16));
-    HIPCHK(rocprim::exclusive_scan(tmp, tmp_bytes, sz, blk_off, 0u, (size_t)nsub,
+    HIPCHK(hipMalloc(&scan_mem.p, tmp_bytes ? tmp_bytes : 16));
+    HIPCHK(rocprim::exclusive_scan(scan_mem.p, tmp_bytes, sz, blk_off, 0u, (size_t)nsub,
                                    rocprim::plus<uint32_t>(), st));
     uint32_t last_off = 0, last_sz = 0;
     HIPCHK(hipMemcpyAsync(&last_off, blk_off + nsub - 1, 4, hipMemcpyDeviceToHost, st));
     HIPCHK(hipMemcpyAsync(&last_sz, sz + nsub - 1, 4, hipMemcpyDeviceToHost, st));
     HIPCHK(hipStreamSynchronize(st));
-    uint64_t total_blk = (uint64_t)last_off + last_sz;
-    // 64-bit check of the 32-bit prefix sum: N*(M+1) bytes plus at most one block of padding each
-    if (((uint64_t)N * (M + 1)) / BLK_ALIGN + (uint64_t)nsub >= (1ull << 32))
-        return fail(IVF_EINVAL, "index too large for 32-bit block offsets");
-    HIPCHK(hipFree(tmp));
-    HIPCHK(hipFree(sz));
+    const uint64_t total_blk = (uint64_t)last_off + last_sz;
     HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->blocks), (size_t)(total_blk ? total_blk : 1) * BLK_ALIGN));
     repack_kernel<<<dim3((unsigned)((nsub * 16 + 255) / 256)), dim3(256), 0, st>>>(
         d->sub_offsets, blk_off, nsub, M, d->codes, d->const_byte, ix->blocks);
@@ -289,8 +295,7 @@ int load_impl(const ivf_index_desc *d, hipStream_t st, ivf_index *ix)
     HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->sub_info), (size_t)nsub * sizeof(uint4)));
     sub_info_kernel<<<dim3((unsigned)((nsub + 255) / 256)), dim3(256), 0, st>>>(d->sub_offsets, blk_off, nsub, ix->sub_info);
     LAUNCHCHK("sub_info_kernel");
-    HIPCHK(hipStreamSynchronize(st));
-    HIPCHK(hipFree(blk_off));
+    HIPCHK(hipStreamSynchronize(st));   // the temporaries are released on return
     return IVF_OK;
 }
 
