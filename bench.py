@@ -25,6 +25,8 @@ DESC_BYTES = 16          # one kept-subregion descriptor read by the scan
 # the same counter reads for the library's plain 1 GiB copy kernel: 2.0 and 1.0).  Measured offline with the
 # commands in profiles/scan_kernel_<workload>.md; None where no counter run has been made.
 MEASURED_SCAN_TRAFFIC_BYTES = {"deep1b": (5_049_329 * 2.0 + 31_660 * 1.0) * 1024}
+# the same for the stage-1 GEMM (profiles/coarse_gemm_<workload>.md)
+MEASURED_GEMM_TRAFFIC_BYTES = {"deep1b": (5_728_405 * 2.0 + 45_316_072 * 1.0) * 1024}
 
 
 def log(msg):
@@ -138,6 +140,14 @@ def main():
     algo_bytes = (codes_scanned * (spec.M + 1) + spec.nq * S * DESC_BYTES) * args.steps / max(scan_launches, 1)
     achieved = algo_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
     coarse_tflops = 2.0 * spec.nq * spec.K * spec.D * args.steps / (stage_ms["coarse_gemm"] * 1e-3) / 1e12
+    # stage 1 must write the distance matrix (reused by the scoring stage) and the block minima, and read the
+    # packed centroid table (4 bytes per component, hi + lo fp16) and the queries once
+    nb = (spec.K + 63) // 64
+    gemm_ms = stage_ms["coarse_gemm"] / max(passes, 1)
+    gemm_bytes = spec.nq * args.steps / max(passes, 1) * (spec.K + nb + spec.D) * 4 + spec.K * spec.D * 4   # per launch
+    gemm_kernel = ("coarse_gemm_skinny_kernel" if spec.nq <= 64 else
+                   "coarse_gemm_sweep_kernel" if spec.K % 128 == 0 and -(-spec.D // 32) * 2 in (6, 8) else "coarse_gemm_kernel")
+    gemm_achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
 
     copy_gbs = None
     if args.calibrate:
@@ -173,6 +183,12 @@ def main():
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_SCAN_TRAFFIC_BYTES.get(spec.name),
                      "launches": scan_launches, "avg_launch_ms": scan_ms, "algorithmic_bytes_per_launch": algo_bytes},
+        # the longest stage, bound by its stores; timed by events around packing + GEMM (packing: a few us)
+        "roofline_coarse_gemm": {"kernel": gemm_kernel, "bound": "hbm", "achieved": gemm_achieved,
+                                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_achieved / HBM_PEAK_GBS,
+                                 "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(spec.name),
+                                 "launches": passes, "avg_launch_ms": gemm_ms,
+                                 "algorithmic_bytes_per_launch": gemm_bytes},
     }
     if copy_gbs is not None:
         result["copy_kernel_gbs_read_plus_write"] = copy_gbs
