@@ -43,6 +43,16 @@ def download_index(desc, spec):
                      h(desc.sub_offsets).view(np.uint32), h(desc.codes), h(desc.const_byte), h(desc.ids))
 
 
+def _omp_threads(n):
+    """Team size of the process's OpenMP runtime (the oracle's loops take the runtime's default)."""
+    import ctypes
+    try:
+        ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+        return True
+    except (OSError, AttributeError):
+        return False
+
+
 def cpu_baseline(ix, Q, spec, budget_s=20.0):
     """The oracle's whole-path search on the host cores, on as many of the same queries as fit the budget."""
     import numpy as np
@@ -59,9 +69,19 @@ def cpu_baseline(ix, Q, spec, budget_s=20.0):
     t = time.time()
     _, _, ns = orc.search(ix, Q[:n], spec.nprobe, tau, spec.k)
     dt = time.time() - t
-    return {"value": n / dt, "unit": "queries/s", "cores": cores, "kind": "oracle",
-            "sample": f"first {n} of {Q.shape[0]} queries of the same workload, full index, {dt:.1f} s wall",
-            "codes_per_s": float(ns.sum()) / dt}
+    out = {"value": n / dt, "unit": "queries/s", "cores": cores, "kind": "oracle",
+           "sample": f"first {n} of {Q.shape[0]} queries of the same workload, full index, {dt:.1f} s wall",
+           "codes_per_s": float(ns.sum()) / dt}
+    # the same on one thread (the kind of figure the paper's timings are), on a few seconds' worth of queries
+    if cores > 1 and _omp_threads(1):
+        n1 = int(min(n, max(2, 4.0 / max(dt / n * cores, 1e-9))))
+        t = time.time()
+        orc.search(ix, Q[:n1], spec.nprobe, tau, spec.k)
+        d1 = time.time() - t
+        _omp_threads(omp)
+        out["single_thread"] = {"value": n1 / d1, "unit": "queries/s", "cores": 1,
+                                "sample": f"first {n1} queries, {d1:.1f} s wall"}
+    return out
 
 
 def main():
@@ -182,7 +202,10 @@ def main():
         "roofline": {"kernel": "scan_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_SCAN_TRAFFIC_BYTES.get(spec.name),
-                     "launches": scan_launches, "avg_launch_ms": scan_ms, "algorithmic_bytes_per_launch": algo_bytes},
+                     "launches": scan_launches, "avg_launch_ms": scan_ms, "algorithmic_bytes_per_launch": algo_bytes,
+                     # the same with 12 instead of this library's 16 bytes counted per descriptor
+                     "frac_at_12B_per_descriptor": (algo_bytes - 4 * spec.nq * S * args.steps / max(scan_launches, 1))
+                                                   / (scan_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if scan_ms > 0 else 0.0},
         # the longest stage, bound by its stores; timed by events around packing + GEMM (packing: a few us)
         "roofline_coarse_gemm": {"kernel": gemm_kernel, "bound": "hbm", "achieved": gemm_achieved,
                                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_achieved / HBM_PEAK_GBS,
