@@ -133,3 +133,35 @@ def test_full_size_deep100m_latency_batches():
 def test_full_size_deep1b_sampled_queries():
     print("case: deep1b full size", flush=True)
     full_size_case("deep1b", 32)
+
+
+@pytest.mark.parametrize("mode", ["zero", "one", "mixed"])
+def test_degenerate_scaling_factors(tiny, mode):
+    """alpha = 0 puts every subcentroid of a region on its centroid (all L scores of a region tie
+    exactly and all points fall into subregion 0: the variant without grouping), alpha = 1 puts
+    them on the neighbouring centroids; 'mixed' alternates 0, 1 and 1/2 between regions."""
+    spec, ix, Q, X = tiny
+    K, N = spec.K, spec.N
+    r3 = np.arange(K) % 3
+    alpha = {"zero": np.zeros(K), "one": np.ones(K),
+             "mixed": np.where(r3 == 0, 0.0, np.where(r3 == 1, 1.0, 0.5))}[mode].astype(np.float32)
+    enc = orc.encode(X, ix.centroids, ix.nbr, alpha, ix.pq_codebook, ix.const_table)
+    perm, off = orc.group(enc.region, enc.sub, spec.L, K)
+    ix2 = orc.Index(spec.D, spec.M, spec.L, K, N, ix.centroids, ix.nbr, alpha, ix.cs_dist2, ix.pq_codebook,
+                    ix.const_table, off, np.ascontiguousarray(enc.codes[perm]),
+                    np.ascontiguousarray(enc.const_byte[perm]), np.arange(N, dtype=np.int32)[perm].copy())
+    if mode == "zero":
+        assert (enc.sub == 0).all()
+    print("case: degenerate alpha", mode, flush=True)
+    run_and_check(ix2, Q, spec, max_near_frac=0.1)
+    run_and_check(ix2, Q, spec, nprobe=spec.K, tau=1.0, k=50, max_near_frac=0.1)
+    # the library's encoder on the same trained index
+    n = 4000
+    desc = parity.to_device(ix2, with_codes=False)
+    region, sub, codes, byte, _ = ivf.ivf_encode(desc, torch.from_numpy(X[:n]).cuda())
+    region, sub, codes = region.cpu().numpy(), sub.cpu().numpy(), codes.cpu().numpy()
+    same = (region == enc.region[:n]) & (sub == enc.sub[:n])
+    assert same.mean() >= 0.99, same.mean()
+    assert (codes[same] == enc.codes[:n][same]).mean() >= 0.999
+    if mode == "zero":
+        assert (sub == 0).all()
