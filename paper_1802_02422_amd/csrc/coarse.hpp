@@ -228,7 +228,8 @@ constexpr int SLD = 64 + 4;   // row stride (floats) of a wavefront's 32x64 outp
 
 // Epilogue of one 32-query x 64-centroid block held by a wavefront as two accumulators
 // (acc[j]: centroids 32j .. 32j+31 of the block): distances max(0, qr + cn + m2 * acc), the
-// block minimum per query into bm, and the distances out through the wavefront's LDS staging
+// block minimum per query into bm (BM_LDS: into the LDS word bm_lds[query of the block * bm_lds_stride]),
+// and the distances out through the wavefront's LDS staging
 // area, [query][centroid], so that 16 lanes cover one query row and every store instruction
 // writes four rows of 256 contiguous bytes, as streaming (non-temporal) stores: the matrix is
 // far larger than the caches and is read back by other kernels only after this one has ended,
@@ -236,10 +237,11 @@ constexpr int SLD = 64 + 4;   // row stride (floats) of a wavefront's 32x64 outp
 // qb / cb: first query / centroid of the block;
 // cnw: the 64 centroid norms of the block (LDS).  EDGE = false skips all bounds checks (the
 // block lies inside Dt and K is a multiple of 4).
-template <bool EDGE, int SROWS = 32>
+template <bool EDGE, int SROWS = 32, bool BM_LDS = false>
 __device__ __forceinline__ void emit_block(const floatx16 (&acc)[2], float qr, float m2, const float *cnw,
                                            float *stage, int64_t qb, int64_t nq, int64_t cb, int64_t K,
-                                           float *__restrict__ Dt, int64_t ldt, float *__restrict__ bm, int nb)
+                                           float *__restrict__ Dt, int64_t ldt, float *__restrict__ bm, int nb,
+                                           float *bm_lds = nullptr, int bm_lds_stride = 0)
 {
     static_assert(SROWS == 32 || SROWS == 16, "the staging area holds 32 or 16 query rows");
     const int lane = threadIdx.x & 63;
@@ -270,7 +272,14 @@ __device__ __forceinline__ void emit_block(const floatx16 (&acc)[2], float qr, f
         }
     m = fminf(m, __shfl_xor(m, 32, WAVE));   // the other half holds the other 32 centroids
     const int64_t q = qb + l32, blk = cb / BMW;
-    if (h == 0 && (!EDGE || (q < nq && blk < nb))) bm[q * nb + blk] = m;
+    if (BM_LDS) {   // the caller collects the minima of several blocks and writes them out as whole sectors
+        // (an explicit instruction: before an ordinary LDS write the compiler may wait for every
+        // outstanding vector-memory operation when direct-to-LDS copies are in flight)
+        const uint32_t at = (uint32_t)reinterpret_cast<uintptr_t>(bm_lds + l32 * bm_lds_stride);   // LDS byte address
+        if (h == 0) asm volatile("ds_write_b32 %0, %1" ::"v"(at), "v"(m) : "memory");
+    } else if (h == 0 && (!EDGE || (q < nq && blk < nb))) {
+        bm[q * nb + blk] = m;
+    }
     // through the staging area, SROWS query rows at a time (the lanes of the other rows sit a pass out)
 #pragma unroll
     for (int pass = 0; pass < 32 / SROWS; ++pass) {
@@ -375,11 +384,18 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) |
 // copy and the step that consumes it, or a lower bound of them (2 copies a step, at least 16
 // stores an epilogue).  With six stages the ring holds a whole tile and every copy is issued
 // ahead of the stores of the tile before the one it belongs to: a wavefront never has to wait
-// for its stores to drain before it can go on, it runs up to one tile ahead of them.  Only whole tiles are handled (nq a multiple of 128 here, K a multiple
-// of 128): the host gives the last, partial query tile to coarse_gemm_kernel.  The workgroup barrier of a step orders LDS traffic only (operands arrive by copies
-// that each wavefront has waited for, nothing else is shared), so it is issued without the
-// global-memory fence of __syncthreads, which would drain the queue at every step.
-constexpr int SWEEP_IL = 2;   // workgroups interleaved over adjacent centroid tiles
+// for its stores to drain before it can go on, it runs up to one tile ahead of them.  Only whole
+// tiles are handled (K a multiple of 128; the rows of a partial last query tile are computed
+// too, into the padding of the per-query buffers).  The workgroup barrier of a step orders LDS
+// traffic only (operands arrive by copies that each wavefront has waited for, nothing else is
+// shared), so it is issued without the global-memory fence of __syncthreads, which would drain
+// the queue at every step.
+//
+// Block minima: a tile gives every query two of them (one per 64-centroid half), 4 bytes each in
+// 128 different rows of bm.  Written directly, those scattered words took a third of the
+// kernel's store-path cycles; they are collected in LDS for SWEEP_BMC consecutive tiles instead
+// and written as 64-byte pieces (16 consecutive blocks of a row).
+constexpr int SWEEP_BMC = 8;   // tiles per write-out of the block minima
 
 template <int STAGES>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void coarse_gemm_sweep_kernel(
@@ -403,28 +419,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __shared__ __attribute__((aligned(16))) float ring5[RING > 5 ? SLOT : 4];
     __shared__ __attribute__((aligned(16))) float stage_all[4 * 16 * SLD];   // 16 query rows per wavefront at a time
     __shared__ __attribute__((aligned(16))) float cns[2][GT];
+    constexpr int BMC = SWEEP_BMC, BMLD = 2 * BMC + 4;     // row stride of the collected minima (floats)
+    __shared__ __attribute__((aligned(16))) float bmbuf[GT * BMLD];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, h = lane >> 5;
     const int wq = (wave >> 1) * 64, wc = (wave & 1) * 64;
 
-    // workgroup -> (query tile, range of centroid tiles): XCD x = b % 8 owns query tiles x, x+8, ...
+    // workgroup -> (query tile, range of centroid tiles): XCD x = b % 8 owns query tiles x, x+8, ...;
+    // step t of the workgroup is centroid tile tb + t
     const int tq_per = (tiles_q + N_XCD - 1) / N_XCD;
     const int xcd = (int)(blockIdx.x % N_XCD);
-    // IL workgroups with consecutive ids share a query tile and take centroid tiles k, k + IL,
-    // k + 2 IL, ... of a group: they start together and advance at the same rate, so at any time
-    // they write IL adjacent 512-byte pieces of the same rows of Dt (longer runs for the L2
-    // write-back and the DRAM pages).  Step j of the workgroup is centroid tile tb + j * IL.
-    constexpr int IL = SWEEP_IL;
     const int64_t local = blockIdx.x / N_XCD;
-    const int k_il = (int)(local % IL);
-    const int64_t rest = local / IL;
-    const int tq = (int)(rest % tq_per) * N_XCD + xcd;
+    const int tq = (int)(local % tq_per) * N_XCD + xcd;
     if (tq >= tiles_q) return;
-    const int tb = (int)(rest / tq_per) * tiles_per_wg * IL + k_il;
+    const int tb = (int)(local / tq_per) * tiles_per_wg;    // a multiple of SWEEP_BMC (the host's tiles_per_wg is)
     const int t_begin = 0;
-    int t_end = tb < tiles_c ? (tiles_c - tb + IL - 1) / IL : 0;      // steps inside the matrix
+    int t_end = tb < tiles_c ? tiles_c - tb : 0;            // steps inside the matrix
     if (t_end > tiles_per_wg) t_end = tiles_per_wg;
     if (t_begin >= t_end) return;
     const int64_t q0 = (int64_t)tq * GT;
@@ -442,7 +454,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     auto issue = [&](int t, int s) {
         if (s >= STAGES) { s -= STAGES; ++t; }
         if (t >= t_end) t = t_end - 1;
-        const float *src = cbase + (int64_t)(tb + t * IL) * GT * Dp + s * DK;
+        const float *src = cbase + (int64_t)(tb + t) * GT * Dp + s * DK;
         float *dst = slot_of(s) + wave * 512;
 #pragma nounroll
         for (int n = 0; n < 2; ++n)
@@ -488,9 +500,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     float *stage = stage_all + wave * (16 * SLD);
 
+    // Writes out the minima collected for steps [t0, t1) (t1 - t0 <= BMC, t0 a multiple of BMC): for each
+    // of the tile's 128 queries the 2 (t1 - t0) consecutive blocks starting at block 2 (tb + t0).  16 lanes
+    // ... 4 lanes cover a row's 64 bytes, one instruction 16 rows.  Every wavefront's minima of these steps
+    // must be in LDS (a workgroup barrier lies between their epilogues and this call).
+    const bool bm_vec = (nb & 3) == 0;                    // rows of bm start on 16-byte boundaries
+    auto flush_bm = [&](int t0, int t1) {
+        const int ncol = 2 * (t1 - t0);
+        const int cq = (tid & 3) * 4;
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            const int row = pass * 64 + (tid >> 2);
+            if (cq < ncol) {
+                const float4 v = *reinterpret_cast<const float4 *>(&bmbuf[row * BMLD + cq]);
+                float *dst = bm + (q0 + row) * (int64_t)nb + (int64_t)(tb + t0) * (GT / BMW) + cq;
+                if (bm_vec && cq + 3 < ncol) {
+                    *reinterpret_cast<float4 *>(dst) = v;
+                } else {
+                    const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (cq + u < ncol) dst[u] = e[u];
+                }
+            }
+        }
+    };
+
     float cn_next = 0.f;
     for (int t = t_begin; t < t_end; ++t) {
-        const int64_t c0 = (int64_t)(tb + t * IL) * GT;
+        const int64_t c0 = (int64_t)(tb + t) * GT;
 #pragma unroll
         for (int s = 0; s < STAGES; ++s) {
             // operations issued after the copy of this stage: the copies of the PD - 1 stages after it,
@@ -504,6 +542,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             if (!WHOLE) issue(t, s + PD);
             else if (s >= 1) issue(t, STAGES + s - 1);
+            // the minima of the last BMC tiles are complete (every wavefront is past their epilogues)
+            if (s == 0 && t > t_begin && (t - t_begin) % BMC == 0) flush_bm(t - t_begin - BMC, t - t_begin);
             // this tile's centroid norms, requested at the end of the previous tile (below), go to LDS
             // in the middle of this one: the stores of the previous epilogue and the copies of the
             // steps since were issued after that load
@@ -540,14 +580,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
         {   // norms of the next tile (index clamped past the end).  The load is hidden from the compiler,
             // which would otherwise drain the whole queue, stores included, where the value is used.
-            const int64_t cnx = c0 + (int64_t)IL * GT + (tid & (GT - 1));
+            const int64_t cnx = c0 + GT + (tid & (GT - 1));
             const float *pn = cn + (cnx < K ? cnx : K - 1);
             asm volatile("global_load_dword %0, %1, off" : "=v"(cn_next) : "v"(pn) : "memory");
         }
         const float *cnw = cns[t & 1] + wc;
 #pragma unroll
         for (int i = 0; i < 2; ++i)
-            emit_block<false, 16>(acc[i], qr[i], m2[i], cnw, stage, q0 + wq + i * 32, nq, c0 + wc, K, Dt, ldt, bm, nb);
+            emit_block<false, 16, true>(acc[i], qr[i], m2[i], cnw, stage, q0 + wq + i * 32, nq, c0 + wc, K, Dt, ldt, bm, nb,
+                                        &bmbuf[(wq + i * 32) * BMLD + ((t - t_begin) % BMC) * 2 + (wave & 1)], BMLD);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -556,6 +597,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // no copy into LDS may outlive the workgroup
+    __syncthreads();                              // the last epilogues' minima are in LDS
+    flush_bm((t_end - t_begin - 1) / BMC * BMC, t_end - t_begin);
 }
 
 // The same for small batches (latency mode): a workgroup takes 32 queries x 256 centroids, all

@@ -136,8 +136,9 @@ int launch_coarse(const _Float16 *xp, const float *xn, const float *xsi, int64_t
         // rows of a partial last query tile are computed too, into the padding every per-query
         // buffer of the coarse stage carries up to a multiple of the tile height.
         const int per_wg = 64;
-        const int64_t groups = (tiles_c + (int64_t)per_wg * SWEEP_IL - 1) / ((int64_t)per_wg * SWEEP_IL);
-        const int64_t g2 = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * groups * SWEEP_IL;
+        static_assert(per_wg % SWEEP_BMC == 0, "a workgroup's first tile starts a 64-byte piece of the block minima");
+        const int64_t groups = (tiles_c + per_wg - 1) / per_wg;
+        const int64_t g2 = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * groups;
         if (g2 >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
         if (stages == 6)
             coarse_gemm_sweep_kernel<6><<<dim3((unsigned)g2), dim3(256), 0, st>>>(xp, xn, xsi, (int64_t)tiles_q * GT, Cp, cn, csi, K, Dt, ldt, bm, nb, tiles_q, (int)tiles_c, per_wg);
