@@ -381,8 +381,9 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
     const size_t sp_lds = (size_t)(PL + 3 * P) * sizeof(uint32_t);
     if (sp_lds > 128 * 1024) return fail(IVF_EINVAL, "nprobe*L=%lld exceeds the 32768 scores one workgroup holds", (long long)PL);
     if (sp_lds > 48 * 1024) {
-        const void *fn = PL > 4096 ? reinterpret_cast<const void *>(&score_prune_kernel<1024>)
-                                   : reinterpret_cast<const void *>(&score_prune_kernel<256>);
+        const void *fn = PL > 16384 ? reinterpret_cast<const void *>(&score_prune_kernel<1024, 8>)
+                         : PL > 4096 ? reinterpret_cast<const void *>(&score_prune_kernel<1024, 4>)
+                                     : reinterpret_cast<const void *>(&score_prune_kernel<256, 4>);
         HIPCHK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sp_lds));
     }
     if (merge_lds > 40 * 1024)
@@ -425,11 +426,14 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
 
         int64_t *ks = kept_sub_out ? kept_sub_out + q0 * S : nullptr;
         int64_t *ns = n_scanned_out ? n_scanned_out + q0 : nullptr;
-        if (PL > 4096)
-            score_prune_kernel<1024><<<dim3((unsigned)n), dim3(1024), sp_lds, st>>>(
+        if (PL > 16384)
+            score_prune_kernel<1024, 8><<<dim3((unsigned)n), dim3(1024), sp_lds, st>>>(
+                Dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, desc, ks, ns);
+        else if (PL > 4096)
+            score_prune_kernel<1024, 4><<<dim3((unsigned)n), dim3(1024), sp_lds, st>>>(
                 Dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, desc, ks, ns);
         else
-            score_prune_kernel<256><<<dim3((unsigned)n), dim3(256), sp_lds, st>>>(
+            score_prune_kernel<256, 4><<<dim3((unsigned)n), dim3(256), sp_lds, st>>>(
                 Dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, desc, ks, ns);
         LAUNCHCHK("score_prune_kernel");
         if ((rc = mark(3))) return rc;

@@ -21,8 +21,13 @@ struct SubDesc {
 // The scores never leave the chip: they are kept in LDS as order-preserving keys.
 // Stage 3: keep the S smallest of the P*L scores by (score, r*L + l).  probe_id is ascending in r, so
 // position order in the score row is subregion-id order and the descriptors come out sorted by address.
-// Dynamic LDS: P*L keys + P probe ids + P probe distances + P alphas.
-template <int BLOCK>
+// The selection leaves the kept score indices, in order, in LDS (over the keys, which every thread
+// holds in registers by then) and their scores in the descriptors; the rest of a descriptor is
+// then filled position by position, consecutive lanes writing consecutive descriptors, with the
+// reads of the subregion table of four positions in flight per thread (filled item by item as
+// they were selected, every read of that table was waited for before the next was issued).
+// Dynamic LDS: P*L keys + P probe ids + P probe distances + P alphas.  P*L <= 4 * MAXV * BLOCK.
+template <int BLOCK, int MAXV>
 __global__ __launch_bounds__(BLOCK) void score_prune_kernel(
     const float *__restrict__ Dt, int64_t ldt, int64_t K, const int32_t *__restrict__ probe_id,
     const float *__restrict__ probe_d, int P, int L, const int32_t *__restrict__ nbr,
@@ -60,20 +65,39 @@ __global__ __launch_bounds__(BLOCK) void score_prune_kernel(
     auto key = [keys](int64_t i) { return keys[i]; };
     uint32_t pivot, need;
     block_radix_select<BLOCK>(key, PL, (uint32_t)S, sh, pivot, need);
+    float *base_of = &desc[q * S].base;                  // stride of one descriptor: 4 floats
+    block_emit_selected_runs<BLOCK, MAXV>(keys, PL, pivot, need, sh,
+                                          [&](uint32_t pos, int64_t i, uint32_t k) {
+                                              keys[pos] = (uint32_t)i;
+                                              base_of[4 * pos] = key_float(k);
+                                          });
+    __syncthreads();
     unsigned long long mine = 0;
-    block_emit_selected_runs<BLOCK>(keys, PL, pivot, need, sh,
-                               [&](uint32_t pos, int64_t i, uint32_t k) {
-                                   const int64_t b = (int64_t)pid[i / L] * L + (i % L);
-                                   const uint4 info = sub_info[b];   // one 16-byte read per kept subregion
-                                   SubDesc d;
-                                   d.blk = info.x;
-                                   d.pos0 = info.y;
-                                   d.len = info.z;
-                                   d.base = key_float(k);
-                                   desc[q * S + pos] = d;
-                                   if (kept_sub) kept_sub[q * S + pos] = b;
-                                   mine += d.len;
-                               });
+    for (int p0 = 0; p0 < S; p0 += 4 * BLOCK) {
+        uint4 info[4];
+        int64_t sub[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int pos = p0 + u * BLOCK + (int)threadIdx.x;
+            if (pos < S) {
+                const int i = (int)keys[pos];
+                sub[u] = (int64_t)pid[i / L] * L + (i % L);
+                info[u] = sub_info[sub[u]];                // one 16-byte read per kept subregion
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int pos = p0 + u * BLOCK + (int)threadIdx.x;
+            if (pos < S) {
+                uint32_t *d = &desc[q * S + pos].blk;      // blk, pos0, len: the first 12 bytes
+                d[0] = info[u].x;
+                d[1] = info[u].y;
+                d[2] = info[u].z;
+                if (kept_sub) kept_sub[q * S + pos] = sub[u];
+                mine += info[u].z;
+            }
+        }
+    }
     if (mine) atomicAdd(&codes_total, mine);
     __syncthreads();
     if (threadIdx.x == 0 && n_scanned) n_scanned[q] = (int64_t)codes_total;

@@ -119,12 +119,13 @@ __device__ uint32_t block_emit_selected(KeyFn key, int64_t n, uint32_t nsel, uin
 // four past n): every thread owns a contiguous run of items, reads it once with 128-bit loads
 // into registers (a run per thread read word by word would put 16 lanes on every bank), counts
 // its selected items, one workgroup scan turns the counts into output offsets, and the thread
-// emits its run in order.  One scan instead of one per BLOCK items.  n <= 32 * BLOCK, n < 65536.
-template <int BLOCK, class EmitFn>
+// emits its run in order.  One scan instead of one per BLOCK items.  n <= 4 * MAXV * BLOCK (MAXV:
+// 128-bit words per thread), n < 65536.  Every key has been read into registers when the first
+// emit runs: emit may overwrite the array.
+template <int BLOCK, int MAXV = 8, class EmitFn>
 __device__ uint32_t block_emit_selected_runs(const uint32_t *keys, int n, uint32_t pivot, uint32_t need,
                                              SelectShared &sh, EmitFn emit)
 {
-    constexpr int MAXV = 8;                                   // 128-bit words per thread
     const int ipt = ((n + BLOCK - 1) / BLOCK + 3) & ~3;       // items per thread, a multiple of 4
     const int i0 = threadIdx.x * ipt;
     uint32_t kv[4 * MAXV];
