@@ -796,9 +796,9 @@ __global__ __launch_bounds__(BLOCK) void probe_select_kernel(const float *__rest
 // centroids little more than P survive), compacted in ascending centroid id, and selected
 // from LDS.  A query with more than PS_CAP survivors (duplicated centroids) takes the
 // global-memory path of probe_select_kernel.  Dynamic LDS: 2P + 3 + max(nb, 2 PS_CAP) words.
-constexpr int PS_NB_MAX = 16384, PS_P_MAX = 256, PS_CAP = 4096, PS_IPT = 2 * PS_P_MAX * BMW / 1024;
+constexpr int PS_NB_MAX = 16384, PS_P_MAX = 256, PS_CAP = 4096;
 
-__global__ __launch_bounds__(1024) void probe_select_lds_kernel(const float *__restrict__ Dt, int64_t ldt,
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void probe_select_lds_kernel(const float *__restrict__ Dt, int64_t ldt,
                                                                 const float *__restrict__ bm, int64_t K,
                                                                 int nb, int P,
                                                                 int32_t *__restrict__ probe_id,
@@ -835,32 +835,58 @@ __global__ __launch_bounds__(1024) void probe_select_lds_kernel(const float *__r
     const uint32_t nselb = P < nb ? (uint32_t)P : (uint32_t)nb;
     uint32_t t, needb;
     block_radix_select<BLOCK>(keyb, nb, nselb, sh, t, needb);
-    uint32_t nflag = block_emit_selected_runs<BLOCK>(keys, nb, t, (uint32_t)P, sh,
+    static_assert(PS_NB_MAX <= 16 * BLOCK && PS_CAP <= 4 * BLOCK, "items per thread of the two ordered emits below");
+    uint32_t nflag = block_emit_selected_runs<BLOCK, 4>(keys, nb, t, (uint32_t)P, sh,
                                                      [&](uint32_t pos, int64_t b, uint32_t) { blist[pos] = (int)b; });
     if (tid == 0) nflag_s = nflag;
     __syncthreads();                                               // blist complete, the block keys are dead
     nflag = nflag_s;
     const uint32_t tf = nb >= P ? t : 0xFFFFFFFFu;                 // fewer blocks than P: no filter
-    const int n_c = (int)nflag * BMW;
-    const int ipt = (n_c + BLOCK - 1) / BLOCK;                     // <= PS_IPT
-    const int i0 = tid * ipt;
-    uint32_t kv[PS_IPT];
-    uint32_t cnt = 0;
+    // Candidates: the 64 distances of every flagged block, a block per wavefront and step (one
+    // 256-byte row piece per load instruction), 16 blocks in flight per wavefront.  Survivors (at or
+    // below the block threshold) are compacted in ascending centroid id: inside a wavefront by
+    // ballots, across wavefronts by one workgroup scan of the wavefronts' counts per round.
+    constexpr int CB = 16;                                         // blocks per wavefront and round
+    const int wave = tid >> 6, lane = tid & 63;
+    uint32_t *sk = keys;
+    int *si = reinterpret_cast<int *>(keys + PS_CAP);
+    uint32_t total = 0;                                            // survivors so far
+    bool overflow = false;
+    for (int b0 = 0; b0 < (int)nflag; b0 += CB * (BLOCK / WAVE)) { // uniform
+        uint32_t kv[CB];
 #pragma unroll
-    for (int j = 0; j < PS_IPT; ++j) {
-        const int v = i0 + j;
-        uint32_t k = 0xFFFFFFFFu;
-        if (j < ipt && v < n_c) {
-            const int64_t c = (int64_t)blist[v >> 6] * BMW + (v & 63);
-            if (c < K) k = float_key(row[c]);
+        for (int j = 0; j < CB; ++j) {
+            const int bi = b0 + wave * CB + j;
+            uint32_t k = 0xFFFFFFFFu;
+            if (bi < (int)nflag) {
+                const int64_t c = (int64_t)blist[bi] * BMW + lane;
+                if (c < K) k = float_key(row[c]);
+            }
+            kv[j] = k;
         }
-        kv[j] = k;
-    }
+        uint32_t wcnt = 0;
 #pragma unroll
-    for (int j = 0; j < PS_IPT; ++j) cnt += (kv[j] <= tf && kv[j] != 0xFFFFFFFFu) ? 1u : 0u;
-    uint32_t total;
-    const uint32_t exc = block_exclusive_scan<BLOCK>(cnt, sh.scan, total);
-    if (total > (uint32_t)PS_CAP || total < (uint32_t)P) {          // uniform; the second cannot happen for nb >= P
+        for (int j = 0; j < CB; ++j) wcnt += (uint32_t)__popcll(__ballot(kv[j] <= tf && kv[j] != 0xFFFFFFFFu));
+        uint32_t round_total;
+        const uint32_t exc = block_exclusive_scan<BLOCK>(lane == 0 ? wcnt : 0u, sh.scan, round_total);
+        if (total + round_total > (uint32_t)PS_CAP) { overflow = true; break; }   // uniform
+        uint32_t at = total + (uint32_t)__builtin_amdgcn_readfirstlane((int)exc);   // the wavefront's next output slot
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+            const bool sel = kv[j] <= tf && kv[j] != 0xFFFFFFFFu;
+            const uint64_t m = __ballot(sel);
+            if (sel) {
+                const uint32_t o = at + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                sk[o] = kv[j];
+                si[o] = blist[b0 + wave * CB + j] * BMW + lane;
+            }
+            at += (uint32_t)__popcll(m);
+        }
+        total += round_total;
+    }
+    if (overflow || total < (uint32_t)P) {                          // uniform; the second cannot happen for nb >= P
+        const int n_c = (int)nflag * BMW;
+        __syncthreads();
         auto key = [&](int64_t v) {
             const int64_t c = (int64_t)blist[v >> 6] * BMW + (v & 63);
             return c < K ? float_key(row[c]) : 0xFFFFFFFFu;
@@ -874,24 +900,11 @@ __global__ __launch_bounds__(1024) void probe_select_lds_kernel(const float *__r
                                    });
         return;
     }
-    uint32_t *sk = keys;
-    int *si = reinterpret_cast<int *>(keys + PS_CAP);
-    {
-        uint32_t at = exc;
-#pragma unroll
-        for (int j = 0; j < PS_IPT; ++j)
-            if (kv[j] <= tf && kv[j] != 0xFFFFFFFFu) {
-                const int v = i0 + j;
-                sk[at] = kv[j];
-                si[at] = blist[v >> 6] * BMW + (v & 63);
-                ++at;
-            }
-    }
     __syncthreads();
     auto skey = [sk](int64_t i) { return sk[i]; };
     uint32_t pivot, need;
     block_radix_select<BLOCK>(skey, (int64_t)total, (uint32_t)P, sh, pivot, need);
-    block_emit_selected_runs<BLOCK>(sk, (int)total, pivot, need, sh,
+    block_emit_selected_runs<BLOCK, 1>(sk, (int)total, pivot, need, sh,
                                     [&](uint32_t pos, int64_t i, uint32_t k) {
                                         probe_id[q * P + pos] = si[i];
                                         probe_d[q * P + pos] = key_float(k);
