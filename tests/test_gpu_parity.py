@@ -100,6 +100,33 @@ def test_coarse_topk_beyond_the_lds_selection_limits():
             assert np.isin(np.nonzero(exact < kth - 2 * tol)[0], gid[q]).all()
 
 
+def test_coarse_topk_with_thousands_of_tied_centroids():
+    """6000 exact copies of one centroid closer to the queries than everything else: every copy ties
+    at the block threshold, more survivors than the LDS selection holds, so the kernel takes its
+    global-memory pass; the P results are the P lowest ids among the copies (ties by id)."""
+    print("case: coarse_topk tied duplicates", flush=True)
+    rng = np.random.default_rng(5)
+    K, D, P = 16384, 96, 64
+    C = rng.standard_normal((K, D)).astype(np.float32)
+    dup = np.sort(rng.choice(K, size=6000, replace=False))
+    C[dup] = C[dup[0]]
+    Q = (C[dup[0]][None, :] + 0.01 * rng.standard_normal((130, D))).astype(np.float32)
+    gid, gd = ivf.ivf_coarse_topk(torch.from_numpy(C).cuda(), torch.from_numpy(Q).cuda(), P)
+    gid, gd = gid.cpu().numpy(), gd.cpu().numpy()
+    assert (gid == dup[:P][None, :]).all()
+    d_true = ((Q.astype(np.float64) - C[dup[0]].astype(np.float64)[None, :]) ** 2).sum(1)
+    u = 2.0 ** -24
+    tol = 16 * u * ((Q.astype(np.float64) ** 2).sum(1) + (C.astype(np.float64) ** 2).sum(1).max())
+    assert (np.abs(gd - d_true[:, None]) <= tol[:, None]).all()
+    assert (gd == gd[:, :1]).all()                       # identical operands give identical distances
+    # the same with fewer copies than the limit: the LDS pass
+    C2 = rng.standard_normal((K, D)).astype(np.float32)
+    dup2 = np.sort(rng.choice(K, size=3000, replace=False))
+    C2[dup2] = C[dup[0]]
+    gid2, _ = ivf.ivf_coarse_topk(torch.from_numpy(C2).cuda(), torch.from_numpy(Q).cuda(), P)
+    assert (gid2.cpu().numpy() == dup2[:P][None, :]).all()
+
+
 def test_search_tiny_all_stages(tiny_gpu):
     spec, ix, Q, X, handle = tiny_gpu
     print("case: search tiny", spec, flush=True)
