@@ -16,8 +16,8 @@ __global__ __launch_bounds__(64) void encode_kernel(
     uint8_t *__restrict__ out_codes, uint8_t *__restrict__ out_byte, float *__restrict__ out_t,
     float *__restrict__ out_res, float *__restrict__ out_mu)
 {
-    extern __shared__ float sm[];
-    float *xs = sm, *cs = sm + D, *es = sm + 2 * D, *mus = sm + 3 * D;
+    extern __shared__ __attribute__((aligned(16))) float sm[];
+    float *xs = sm, *cs = sm + D, *es = sm + 2 * D, *mus = sm + 3 * D;   // D is a multiple of 4: all 16-byte aligned
     const int lane = threadIdx.x;
     const int64_t i = blockIdx.x;
     if (i >= n) return;
@@ -31,26 +31,76 @@ __global__ __launch_bounds__(64) void encode_kernel(
 
     // Eq. (3) through the closed form of the subcentroid distance:
     // ||x - mu_l||^2 = (1-a)||x-c||^2 + a||x-s_l||^2 - a(1-a)||c-s_l||^2
+    // Four neighbour rows at a time, 16 lanes per row, a lane taking every 16th group of four
+    // components: a load instruction then reads four rows of up to 256 contiguous bytes (with a
+    // lane per neighbour it touched 64 different rows, and the kernel was bounded by the number
+    // of cache lines its loads addressed).
+    const int D4 = D >> 2;
+    const int g = lane >> 4, c16 = lane & 15;
     float dxc = 0.f;
-    for (int t = 0; t < D; ++t) {
-        float u = xs[t] - cs[t];
-        dxc = fmaf(u, u, dxc);
+    for (int cc = lane; cc < D4; cc += WAVE) {
+        const float4 xv = *reinterpret_cast<const float4 *>(xs + 4 * cc);
+        const float4 cv = *reinterpret_cast<const float4 *>(cs + 4 * cc);
+        const float u0 = xv.x - cv.x, u1 = xv.y - cv.y, u2 = xv.z - cv.z, u3 = xv.w - cv.w;
+        dxc = fmaf(u0, u0, dxc);
+        dxc = fmaf(u1, u1, dxc);
+        dxc = fmaf(u2, u2, dxc);
+        dxc = fmaf(u3, u3, dxc);
     }
+    dxc = wave_sum(dxc);
     float best = INFINITY;
     int best_l = 0x7fffffff;
-    for (int l = lane; l < L; l += WAVE) {
-        const float *s = C + (int64_t)nbr[r * L + l] * D;
-        float dxs = 0.f;
-        for (int t = 0; t < D; t += 4) {
-            float4 sv = *reinterpret_cast<const float4 *>(s + t);
-            float u0 = xs[t] - sv.x, u1 = xs[t + 1] - sv.y, u2 = xs[t + 2] - sv.z, u3 = xs[t + 3] - sv.w;
-            dxs = fmaf(u0, u0, dxs);
-            dxs = fmaf(u1, u1, dxs);
-            dxs = fmaf(u2, u2, dxs);
-            dxs = fmaf(u3, u3, dxs);
+    for (int lb = 0; lb < L; lb += WAVE) {            // 64 neighbours at a time: their ids in one load
+        const int my_nbr = lb + lane < L ? nbr[r * L + lb + lane] : 0;
+        const float my_cs = lb + lane < L ? cs_dist2[r * L + lb + lane] : 0.f;
+        const int nl = L - lb < WAVE ? L - lb : WAVE;
+        for (int l0 = 0; l0 < nl; l0 += 16) {         // four steps of four rows, their loads issued together
+            float4 sv[4][2];
+            const float4 *s4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t row = __shfl(my_nbr, (l0 + 4 * u + g) & (WAVE - 1), WAVE);
+                s4[u] = reinterpret_cast<const float4 *>(C + row * D);
+                const bool live = l0 + 4 * u + g < nl;
+                sv[u][0] = live && c16 < D4 ? s4[u][c16] : make_float4(0.f, 0.f, 0.f, 0.f);
+                sv[u][1] = live && c16 + 16 < D4 ? s4[u][c16 + 16] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int lw = l0 + 4 * u + g;          // neighbour within this batch of 64
+                const bool live = lw < nl;
+                const float csl = __shfl(my_cs, lw & (WAVE - 1), WAVE);
+                float dxs = 0.f;
+                if (live) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        if (c16 + 16 * h < D4) {
+                            const float4 xv = *reinterpret_cast<const float4 *>(xs + 4 * (c16 + 16 * h));
+                            const float u0 = xv.x - sv[u][h].x, u1 = xv.y - sv[u][h].y, u2 = xv.z - sv[u][h].z,
+                                        u3 = xv.w - sv[u][h].w;
+                            dxs = fmaf(u0, u0, dxs);
+                            dxs = fmaf(u1, u1, dxs);
+                            dxs = fmaf(u2, u2, dxs);
+                            dxs = fmaf(u3, u3, dxs);
+                        }
+                    for (int cc = c16 + 32; cc < D4; cc += 16) {   // D > 128
+                        const float4 sw = s4[u][cc];
+                        const float4 xv = *reinterpret_cast<const float4 *>(xs + 4 * cc);
+                        const float u0 = xv.x - sw.x, u1 = xv.y - sw.y, u2 = xv.z - sw.z, u3 = xv.w - sw.w;
+                        dxs = fmaf(u0, u0, dxs);
+                        dxs = fmaf(u1, u1, dxs);
+                        dxs = fmaf(u2, u2, dxs);
+                        dxs = fmaf(u3, u3, dxs);
+                    }
+                }
+#pragma unroll
+                for (int o = 8; o > 0; o >>= 1) dxs += __shfl_xor(dxs, o, WAVE);   // over the 16 lanes of the row
+                if (live && c16 == 0) {
+                    const float sc = fmaf(a, dxs, fmaf(1.f - a, dxc, -a * (1.f - a) * csl));
+                    if (sc < best) { best = sc; best_l = lb + lw; }
+                }
+            }
         }
-        float sc = fmaf(a, dxs, fmaf(1.f - a, dxc, -a * (1.f - a) * cs_dist2[r * L + l]));
-        if (sc < best) { best = sc; best_l = l; }
     }
     wave_argmin(best, best_l);
     if (lane == 0) out_sub[i] = best_l;
