@@ -42,10 +42,12 @@ def test_coarse_topk_matches_bruteforce(tiny):
         assert (np.abs(gd - d_true) <= np.maximum(1e-4 * d_true, at[:, None])).all()
 
 
-@pytest.mark.parametrize("D,K,nq", [(20, 300, 1), (96, 1280, 65), (100, 1000, 128), (128, 1024, 200), (96, 2560, 300)])
+@pytest.mark.parametrize("D,K,nq", [(20, 300, 1), (96, 1280, 65), (100, 1000, 128), (128, 1024, 200), (96, 2560, 300),
+                                    (96, 1152, 200), (96, 384, 130), (128, 9 * 128, 70)])
 def test_coarse_distances_within_fp32_bound_for_all_kernel_variants(D, K, nq):
     """Shapes that reach every variant of the coarse kernel (small batch, generic tile with a
-    padded width, swept tiles with a partial last query tile), rows of very different
+    padded width, swept tiles with a partial last query tile, with fewer tiles than one write-out
+    of the block minima covers and with rows of block minima that are not 16-byte aligned), rows of very different
     magnitude, exact duplicates: every returned distance is within 16 u (|q|^2 + max |c|^2) of
     the fp64 value, and the P returned regions are the exact ones up to ties inside that bound."""
     print("case: coarse variants", D, K, nq, flush=True)
