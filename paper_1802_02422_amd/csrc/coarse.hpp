@@ -622,7 +622,13 @@ __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
     __shared__ __attribute__((aligned(16))) float ops1[OPS];
     __shared__ __attribute__((aligned(16))) float cns[SKC];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int64_t q0 = (int64_t)(blockIdx.x % tiles_q) * SKQ, c0 = (int64_t)(blockIdx.x / tiles_q) * SKC;
+    // The query tiles of one block of 256 centroids go to the same XCD (workgroup b runs on XCD b % 8),
+    // one after the other: the centroid rows are fetched from HBM once and found in that XCD's L2 by
+    // the other tiles.  Grid: 8 * ceil(blocks / 8) * tiles_q workgroups.
+    const int64_t local = blockIdx.x / N_XCD;
+    const int64_t cblk = (local / tiles_q) * N_XCD + blockIdx.x % N_XCD;
+    const int64_t q0 = (local % tiles_q) * SKQ, c0 = cblk * SKC;
+    if (c0 >= K) return;                                           // (before any barrier; uniform)
     const int wc = wave * 64;
     const int l32 = lane & 31, h = lane >> 5;
     cns[tid] = c0 + tid < K ? cn[c0 + tid] : 0.f;
