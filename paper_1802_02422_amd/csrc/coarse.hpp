@@ -601,14 +601,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     flush_bm((t_end - t_begin - 1) / BMC * BMC, t_end - t_begin);
 }
 
-// The same for small batches (latency mode): a workgroup takes 32 queries x 256 centroids, all
-// four wavefronts share the 32 queries and each owns 64 of the centroids (two accumulators),
-// so a batch of up to 32 queries costs a quarter of the MFMA work of the 128-query tile and
-// the kernel is bounded by streaming the centroid matrix once per 32 queries.  Operand rows
-// in LDS: 32 query rows then 256 centroid rows per buffer, staged like the large tile.
+// The same for small batches (latency mode): a workgroup takes 32 QT queries x 256 centroids (QT = 1
+// or 2), all four wavefronts share the queries and each owns 64 of the centroids (2 QT
+// accumulators), so a batch of up to 32 queries costs a quarter of the MFMA work of the
+// 128-query tile and the kernel is bounded by streaming the centroid matrix once per batch of
+// up to 64 queries.  Operand rows in LDS: the query rows, then 256 centroid rows per buffer,
+// staged like the large tile.
 constexpr int SKQ = 32, SKC = 256;
-constexpr int SKBUF = (SKQ + SKC) * ROWF;   // floats per operand buffer
 
+template <int QT>
 __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
     const _Float16 *__restrict__ Qp, const float *__restrict__ qn, const float *__restrict__ qsi, int64_t nq,
     const _Float16 *__restrict__ Cp, const float *__restrict__ cn, const float *__restrict__ csi, int64_t K,
@@ -616,6 +617,9 @@ __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
 {
     typedef const __attribute__((address_space(1))) void *gptr_t;
     typedef __attribute__((address_space(3))) void *lptr_t;
+    static_assert(QT == 1 || QT == 2, "one or two blocks of 32 queries");
+    constexpr int QROWS = QT * SKQ;
+    constexpr int SKBUF = (QROWS + SKC) * ROWF;   // floats per operand buffer
     // two operand buffers, each reused as the output staging of two wavefronts
     constexpr int OPS = SKBUF > 2 * 32 * SLD ? SKBUF : 2 * 32 * SLD;
     __shared__ __attribute__((aligned(16))) float ops0[OPS];
@@ -627,36 +631,40 @@ __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
     // the other tiles.  Grid: 8 * ceil(blocks / 8) * tiles_q workgroups.
     const int64_t local = blockIdx.x / N_XCD;
     const int64_t cblk = (local / tiles_q) * N_XCD + blockIdx.x % N_XCD;
-    const int64_t q0 = (local % tiles_q) * SKQ, c0 = cblk * SKC;
+    const int64_t q0 = (local % tiles_q) * QROWS, c0 = cblk * SKC;
     if (c0 >= K) return;                                           // (before any barrier; uniform)
     const int wc = wave * 64;
     const int l32 = lane & 31, h = lane >> 5;
     cns[tid] = c0 + tid < K ? cn[c0 + tid] : 0.f;
-    floatx16 acc[2];
+    floatx16 acc[QT][2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int i = 0; i < QT; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     // Copies per stage: wave w takes the centroid blocks (16 rows each) w, w+4, w+8, w+12 with one
-    // instruction in a rolled loop, waves 0 and 1 also one block of query rows (see gemm_tile).
+    // instruction in a rolled loop, the first 2 QT waves also one block of query rows (see gemm_tile).
     const int rl = lane >> 2;
     const int fq = (lane & 3) ^ ((rl >> 2) & 3);                       // (r >> 2) & 3 depends on the row inside the block only
     const float *srcc = reinterpret_cast<const float *>(Cp) + (c0 + wave * 16 + rl) * Dp + fq * 4;
-    const float *srcq = reinterpret_cast<const float *>(Qp) + (q0 + (wave & 1) * 16 + rl) * Dp + fq * 4;
+    const float *srcq = reinterpret_cast<const float *>(Qp) + (q0 + (wave & (2 * QT - 1)) * 16 + rl) * Dp + fq * 4;
     auto issue = [&](int k0, float *dst) {
 #pragma nounroll
         for (int n = 0; n < 4; ++n)
             __builtin_amdgcn_global_load_lds((gptr_t)(srcc + (int64_t)n * 64 * Dp + k0),
-                                             (lptr_t)(dst + (2 + wave + 4 * n) * 256), 16, 0, 0);
-        if (wave < 2)
+                                             (lptr_t)(dst + (2 * QT + wave + 4 * n) * 256), 16, 0, 0);
+        if (wave < 2 * QT)
             __builtin_amdgcn_global_load_lds((gptr_t)(srcq + k0), (lptr_t)(dst + wave * 256), 16, 0, 0);
     };
     auto compute = [&](const float *As) {
-        const float *Bs = As + SKQ * ROWF;
-        gu32x4 a[2], b[2][2];
+        const float *Bs = As + QROWS * ROWF;
+        gu32x4 a[QT][2], b[2][2];
 #pragma unroll
-        for (int p = 0; p < 2; ++p)
-            a[p] = *reinterpret_cast<const gu32x4 *>(&As[l32 * ROWF + (((2 * h + p) ^ ((l32 >> 2) & 3)) << 2)]);
+        for (int i = 0; i < QT; ++i)
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+                a[i][p] = *reinterpret_cast<const gu32x4 *>(&As[(i * 32 + l32) * ROWF + (((2 * h + p) ^ ((l32 >> 2) & 3)) << 2)]);
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int rb = wc + j * 32 + l32;
@@ -667,7 +675,9 @@ __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
 #pragma unroll
         for (int e = 0; e < 3; ++e)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) acc[j] = mfma3(b[j], a, acc[j], e);
+            for (int i = 0; i < QT; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = mfma3(b[j], a[i], acc[i][j], e);
     };
     const int stages = Dp / DK;
     issue(0, ops0);
@@ -684,12 +694,15 @@ __global__ __launch_bounds__(256) void coarse_gemm_skinny_kernel(
     __syncthreads();
     const float m2c = -2.f * csi[0];
     float *stage = (wave < 2 ? ops0 : ops1) + (wave & 1) * (32 * SLD);
-    const int64_t q = q0 + l32;
-    const float qr = q < nq ? qn[q] : 0.f;
-    const float m2 = q < nq ? m2c * qsi[q] : 0.f;
-    const bool interior = q0 + SKQ <= nq && c0 + SKC <= K && (K & 3) == 0;
-    if (interior) emit_block<false>(acc, qr, m2, cns + wc, stage, q0, nq, c0 + wc, K, Dt, ldt, bm, nb);
-    else emit_block<true>(acc, qr, m2, cns + wc, stage, q0, nq, c0 + wc, K, Dt, ldt, bm, nb);
+    const bool interior = q0 + QROWS <= nq && c0 + SKC <= K && (K & 3) == 0;
+#pragma unroll
+    for (int i = 0; i < QT; ++i) {
+        const int64_t qb = q0 + i * 32, q = qb + l32;
+        const float qr = q < nq ? qn[q] : 0.f;
+        const float m2 = q < nq ? m2c * qsi[q] : 0.f;
+        if (interior) emit_block<false>(acc[i], qr, m2, cns + wc, stage, qb, nq, c0 + wc, K, Dt, ldt, bm, nb);
+        else emit_block<true>(acc[i], qr, m2, cns + wc, stage, qb, nq, c0 + wc, K, Dt, ldt, bm, nb);
+    }
 }
 
 // Nearest centroid only (P = 1): the same tile product, reduced on the fly to

@@ -119,11 +119,13 @@ int launch_coarse(const _Float16 *xp, const float *xn, const float *xsi, int64_t
 {
     const int64_t ldt = dt_stride(K);
     const int nb = (int)((K + BMW - 1) / BMW);
-    if (nq <= 2 * SKQ) {   // small batch: 32-query tiles
-        int tiles_q = (int)((nq + SKQ - 1) / SKQ);
+    if (nq <= 2 * SKQ) {   // small batch: one tile of 32 or 64 queries, the centroid table streamed once
         const int64_t cblocks = (K + SKC - 1) / SKC;
-        int64_t grid = (cblocks + N_XCD - 1) / N_XCD * N_XCD * tiles_q;
-        coarse_gemm_skinny_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xp, xn, xsi, nq, Cp, cn, csi, K, Dp, Dt, ldt, bm, nb, tiles_q);
+        const int64_t grid = (cblocks + N_XCD - 1) / N_XCD * N_XCD;
+        if (nq <= SKQ)
+            coarse_gemm_skinny_kernel<1><<<dim3((unsigned)grid), dim3(256), 0, st>>>(xp, xn, xsi, nq, Cp, cn, csi, K, Dp, Dt, ldt, bm, nb, 1);
+        else
+            coarse_gemm_skinny_kernel<2><<<dim3((unsigned)grid), dim3(256), 0, st>>>(xp, xn, xsi, nq, Cp, cn, csi, K, Dp, Dt, ldt, bm, nb, 1);
         LAUNCHCHK("coarse_gemm_skinny_kernel");
         return IVF_OK;
     }
