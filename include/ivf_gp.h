@@ -114,7 +114,12 @@ int ivf_set_scratch_limit(ivf_index *index, int64_t bytes);
  * half (22 significant bits) and accumulated in fp32, which is as accurate
  * as an fp32 dot product.
  * Asynchronous on hip_stream; the handle's scratch is reused by every call,
- * so calls on one handle must not overlap.
+ * so calls on one handle must not overlap.  The scratch grows on demand: a
+ * call that needs more of it than any call before synchronizes the device,
+ * frees and re-allocates; a call that fits what is there allocates nothing,
+ * clears nothing with memset nodes and can be captured into a HIP graph (a
+ * graph captured earlier holds the old addresses and is void once a later
+ * call has grown the scratch).
  */
 int ivf_search(ivf_index *index, const float *queries, int64_t nq, int nprobe, float prune_frac,
                int k, int32_t *out_ids, float *out_dists, void *hip_stream);

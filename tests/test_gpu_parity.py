@@ -161,6 +161,39 @@ def test_search_is_deterministic_and_matches_plain_entry(tiny_gpu):
     assert torch.equal(ids, a["ids"]) and torch.equal(d, a["dists"])
 
 
+def test_search_replays_from_a_captured_graph(tiny_gpu):
+    """Once its scratch buffers exist a search neither allocates nor clears memory with memset nodes:
+    it can be captured into a HIP graph.  Every replay, with eager searches of other shapes in
+    between, returns the bits of the eager call."""
+    spec, ix, Q, X, handle = tiny_gpu
+    print("case: graph capture", flush=True)
+    Qd = torch.from_numpy(Q).cuda()
+    ids = torch.empty((len(Q), spec.k), dtype=torch.int32, device="cuda")
+    d = torch.empty((len(Q), spec.k), dtype=torch.float32, device="cuda")
+    ivf.ivf_search(handle, Qd, spec.nprobe, spec.prune_frac, spec.k, ids, d)      # sizes the scratch buffers
+    torch.cuda.synchronize()
+    ref_ids, ref_d = ids.clone(), d.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ivf.ivf_search(handle, Qd, spec.nprobe, spec.prune_frac, spec.k, ids, d)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ivf.ivf_search(handle, Qd, spec.nprobe, spec.prune_frac, spec.k, ids, d)
+    for rep in range(4):
+        ids.fill_(-7)
+        d.fill_(-7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ids, ref_ids) and torch.equal(d, ref_d), rep
+        ivf.ivf_search(handle, Qd[: 3 + rep].contiguous(), 5 + rep, 1.0, 7)     # the program's own eager work in between
+        torch.cuda.synchronize()
+    del graph
+
+
 def test_query_tiling_gives_identical_results(tiny_gpu):
     spec, ix, Q, X, handle = tiny_gpu
     Qd = torch.from_numpy(Q).cuda()
