@@ -501,9 +501,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     float *stage = stage_all + wave * (16 * SLD);
 
     // Writes out the minima collected for steps [t0, t1) (t1 - t0 <= BMC, t0 a multiple of BMC): for each
-    // of the tile's 128 queries the 2 (t1 - t0) consecutive blocks starting at block 2 (tb + t0).  16 lanes
-    // ... 4 lanes cover a row's 64 bytes, one instruction 16 rows.  Every wavefront's minima of these steps
-    // must be in LDS (a workgroup barrier lies between their epilogues and this call).
+    // of the tile's 128 queries the 2 (t1 - t0) consecutive blocks starting at block 2 (tb + t0).  Four
+    // lanes cover a row's 64 bytes, one store instruction 16 rows.  Every wavefront's minima of these
+    // steps must be in LDS (a workgroup barrier lies between their epilogues and this call).
     const bool bm_vec = (nb & 3) == 0;                    // rows of bm start on 16-byte boundaries
     auto flush_bm = [&](int t0, int t1) {
         const int ncol = 2 * (t1 - t0);
