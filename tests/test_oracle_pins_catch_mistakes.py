@@ -66,6 +66,22 @@ MUTATIONS = {
         "s += 2.0 * mu[i * D + m * ds + c] * r + r * r;",
         "s += mu[i * D + m * ds + c] * r + r * r;",
         ["test_scan_equals_distance_to_explicitly_decoded_points", "test_sub_assign_and_encode_against_numpy_bruteforce"]),
+    "prune_subregion_id": (
+        "sid[p * L + l] = (int64_t)probe_id[q * P + p] * L + l;",
+        "sid[p * L + l] = (int64_t)p * L + l;",
+        ["test_prune_is_global_bruteforce_sort"]),
+    "select_tie_by_position": (
+        "tie[i] = ids[cand_pos[i]];",
+        "tie[i] = cand_pos[i];",
+        ["test_select_bruteforce_and_padding"]),
+    "pq_codeword_block": (
+        "double u = E[i * D + m * ds + t] - (double)codebook[((int64_t)m * 256 + j) * ds + t];",
+        "double u = E[i * D + m * ds + t] - (double)codebook[((int64_t)j * ds) + t];",
+        ["test_sub_assign_and_encode_against_numpy_bruteforce"]),
+    "quantiser_tie_rule": (
+        "            double d = fabs(t[i] - (double)table[j]);\n            if (d < best) { best = d; bj = j; }",
+        "            double d = fabs(t[i] - (double)table[j]);\n            if (d <= best) { best = d; bj = j; }",
+        ["test_scalar_quantiser"]),
     "subcentroid_weights": (
         "double mu = (double)c[t] + a * ((double)s[t] - (double)c[t]);",
         "double mu = (double)c[t] + (1.0 - a) * ((double)s[t] - (double)c[t]);",
