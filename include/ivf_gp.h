@@ -33,6 +33,8 @@ extern "C" {
 /* limits of this build */
 #define IVF_MAX_K_RESULTS 1024   /* k of ivf_search */
 #define IVF_MAX_D         1024
+#define IVF_MAX_SCORES    32768  /* nprobe * L of a search: the scores of one query stay in LDS */
+#define IVF_NOALLOC_SCRATCH_BYTES (64 << 20)   /* static scratch of ivf_search_noalloc, per GPU */
 
 typedef struct ivf_index ivf_index; /* opaque */
 
@@ -108,7 +110,8 @@ int ivf_set_scratch_limit(ivf_index *index, int64_t bytes);
  * out_ids [nq][k] int32 and out_dists [nq][k] fp32 (estimated squared L2
  * distance); rows with fewer than k candidates are padded with id -1 and
  * +inf.  1 <= nprobe <= min(K, 4096), 0 < prune_frac <= 1,
- * 1 <= k <= IVF_MAX_K_RESULTS, nprobe*L <= 32000.  All results are fp32 and
+ * 1 <= k <= IVF_MAX_K_RESULTS, nprobe*L <= IVF_MAX_SCORES and
+ * nprobe*(L+3) <= 39424 (LDS of one workgroup).  All results are fp32 and
  * carry fp32 rounding errors; the inner products <q, c> of stage 1 are
  * formed on the fp16 matrix units from operands split into a high and a low
  * half (22 significant bits) and accumulated in fp32, which is as accurate
@@ -123,6 +126,24 @@ int ivf_set_scratch_limit(ivf_index *index, int64_t bytes);
  */
 int ivf_search(ivf_index *index, const float *queries, int64_t nq, int nprobe, float prune_frac,
                int k, int32_t *out_ids, float *out_dists, void *hip_stream);
+
+/*
+ * ivf_search for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and bit-identical results, but every intermediate
+ * buffer (distance tile, block minima, packed queries, probes, descriptors,
+ * lookup tables, partial top-k lists) is carved out of one static device array
+ * of IVF_NOALLOC_SCRATCH_BYTES that each GPU holds from the moment the library
+ * is loaded until the process ends.  The call makes no hipMalloc / hipFree and
+ * calls no allocating routine; the whole batch is one pass, and a batch whose
+ * buffers do not fit (roughly nq * K * 4.1 bytes + nq * 40 KB: 15 queries at
+ * K = 2^20, 230 at K = 65 536) is rejected with IVF_EINVAL before anything is
+ * launched.  Nothing in the array has to start at zero.  All calls on one GPU
+ * share that GPU's array, whatever the handle or stream: calls that overlap
+ * on one GPU race; order them on one stream or with events.
+ */
+int ivf_search_noalloc(ivf_index *index, const float *queries, int64_t nq, int nprobe, float prune_frac,
+                       int k, int32_t *out_ids, float *out_dists, void *hip_stream);
 
 /*
  * ivf_search that also exports the intermediate results of stages 1, 3 and 5

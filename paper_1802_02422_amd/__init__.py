@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     ivf_set_scratch_limit,
     ivf_search,
     ivf_search_stages,
+    ivf_search_noalloc,
     ivf_num_kept,
     ivf_coarse_topk,
     ivf_encode,

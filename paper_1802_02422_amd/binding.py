@@ -50,6 +50,7 @@ def load_library():
     lib.ivf_free_index.restype = None
     lib.ivf_set_scratch_limit.argtypes = [vp, i64]
     lib.ivf_search.argtypes = [vp, vp, i64, i32, f32, i32, vp, vp, vp]
+    lib.ivf_search_noalloc.argtypes = [vp, vp, i64, i32, f32, i32, vp, vp, vp]
     lib.ivf_search_stages.argtypes = [vp, vp, i64, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.ivf_num_kept.argtypes = [i32, i32, f32]
     lib.ivf_num_kept.restype = i64
@@ -181,6 +182,18 @@ def ivf_search(index: IndexHandle, queries: torch.Tensor, nprobe: int, prune_fra
     _dev(out_dists, torch.float32, "out_dists", (nq, k))
     _check(load_library().ivf_search(index.ptr, _ptr(queries), nq, nprobe, prune_frac, k,
                                      _ptr(out_ids), _ptr(out_dists), _stream()))
+    return out_ids, out_dists
+
+
+def ivf_search_noalloc(index: IndexHandle, queries: torch.Tensor, nprobe: int, prune_frac: float, k: int,
+                       out_ids: torch.Tensor, out_dists: torch.Tensor):
+    """ivf_search on the library's static scratch array: the call allocates nothing (outputs are the caller's)."""
+    nq = queries.shape[0]
+    _dev(queries, torch.float32, "queries", (nq, index.D))
+    _dev(out_ids, torch.int32, "out_ids", (nq, k))
+    _dev(out_dists, torch.float32, "out_dists", (nq, k))
+    _check(load_library().ivf_search_noalloc(index.ptr, _ptr(queries), nq, nprobe, prune_frac, k,
+                                             _ptr(out_ids), _ptr(out_dists), _stream()))
     return out_ids, out_dists
 
 

@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -177,6 +178,66 @@ int launch_probe_select(const float *Dt, const float *bm, int64_t nq, int64_t K,
     return IVF_OK;
 }
 
+// Device scratch of one pass over a tile of queries, and the launch shape that goes with it.
+struct SearchWs {
+    float *dt = nullptr, *bm = nullptr, *qn = nullptr, *qsi = nullptr;
+    _Float16 *qpk = nullptr;
+    int32_t *probe_id = nullptr;
+    float *probe_d = nullptr;
+    SubDesc *desc = nullptr;
+    float *lut = nullptr;
+    uint64_t *partial = nullptr;
+};
+
+enum { WS_DT, WS_BM, WS_QN, WS_QSI, WS_QPK, WS_PID, WS_PD, WS_DESC, WS_LUT, WS_PARTIAL, WS_COUNT };
+
+struct SearchPlan {
+    int64_t tile = 0;            // queries per pass
+    int S = 0, nsplit = 1, n_lists = 0, merge_n = 0, merge_pow2 = 0;
+    size_t bytes[WS_COUNT] = {};
+};
+
+// Rows of the distance tile (and of the block minima) a pass over n queries may write: the sweep
+// kernel works on whole tiles of GT query rows, the other two check every row.
+int64_t dt_rows(int64_t n, int64_t K, int Dp)
+{
+    const int stages = Dp / DK;
+    const bool sweep = n > 2 * SKQ && (stages == 6 || stages == 8) && K % GT == 0;
+    return sweep ? (n + GT - 1) / GT * GT : n;
+}
+
+SearchPlan plan_search(int64_t K, int D, int M, int P, int S, int k, int64_t tile)
+{
+    SearchPlan pl;
+    pl.tile = tile;
+    pl.S = S;
+    // workgroups per query in the scan: fill the chip when the batch is small
+    int nsplit = (int)((2048 + tile - 1) / tile);
+    if (nsplit > 64) nsplit = 64;
+    if (nsplit > (S + 15) / 16) nsplit = (S + 15) / 16;
+    while (nsplit > 1 && (int64_t)nsplit * SCAN_WAVES * k > 8192) --nsplit;
+    if (nsplit < 1) nsplit = 1;
+    pl.nsplit = nsplit;
+    pl.n_lists = nsplit * SCAN_WAVES;
+    pl.merge_n = pl.n_lists * k;
+    pl.merge_pow2 = next_pow2(pl.merge_n);
+    const int Dp = packed_dim(D);
+    const size_t rows = (size_t)dt_rows(tile, K, Dp);
+    const size_t tile_pad = (size_t)packed_rows(tile);   // the GEMM tiles copy whole tiles of packed rows
+    const int64_t nb = (K + BMW - 1) / BMW;
+    pl.bytes[WS_DT] = rows * dt_stride(K) * sizeof(float);
+    pl.bytes[WS_BM] = rows * nb * sizeof(float);
+    pl.bytes[WS_QN] = tile_pad * sizeof(float);
+    pl.bytes[WS_QSI] = tile_pad * sizeof(float);
+    pl.bytes[WS_QPK] = tile_pad * Dp * 2 * sizeof(_Float16);
+    pl.bytes[WS_PID] = (size_t)tile * P * sizeof(int32_t);
+    pl.bytes[WS_PD] = (size_t)tile * P * sizeof(float);
+    pl.bytes[WS_DESC] = (size_t)tile * S * sizeof(SubDesc);
+    pl.bytes[WS_LUT] = (size_t)tile * M * 256 * sizeof(float);
+    pl.bytes[WS_PARTIAL] = (size_t)tile * pl.merge_n * sizeof(uint64_t);
+    return pl;
+}
+
 }  // namespace
 
 struct ivf_index {
@@ -327,10 +388,22 @@ extern "C" int ivf_load_index(const ivf_index_desc *d, void *hip_stream, ivf_ind
     return IVF_OK;
 }
 
-extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq, int nprobe,
-                                 float prune_frac, int k, int32_t *out_ids, float *out_dists,
-                                 int32_t *probe_id_out, float *probe_d_out, int64_t *kept_sub_out,
-                                 int64_t *n_scanned_out, void *hip_stream)
+namespace {
+
+struct SearchArgs {
+    const float *queries;
+    int64_t nq;
+    int P, k, S;
+    int32_t *out_ids;
+    float *out_dists;
+    int32_t *probe_id_out;
+    float *probe_d_out;
+    int64_t *kept_sub_out;
+    int64_t *n_scanned_out;
+};
+
+int check_search_args(const ivf_index *ix, const float *queries, int64_t nq, int nprobe, float prune_frac, int k,
+                      const int32_t *out_ids, const float *out_dists)
 {
     if (!ix) return fail(IVF_EINVAL, "index is NULL");
     if (nq < 0 || nq >= (1ll << 31)) return fail(IVF_EINVAL, "nq=%lld out of range", (long long)nq);
@@ -341,11 +414,144 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
         return fail(IVF_EINVAL, "nprobe=%d must be in [1, min(K, 4096)]", nprobe);
     if (!(prune_frac > 0.f) || prune_frac > 1.f) return fail(IVF_EINVAL, "prune_frac must be in (0, 1]");
     if (k < 1 || k > IVF_MAX_K_RESULTS) return fail(IVF_EINVAL, "k=%d must be in [1, %d]", k, IVF_MAX_K_RESULTS);
-    const int P = nprobe, L = ix->L, M = ix->M, D = ix->D;
+    const int64_t PL = (int64_t)nprobe * ix->L;
+    if (PL > IVF_MAX_SCORES) return fail(IVF_EINVAL, "nprobe*L=%lld exceeds %d", (long long)PL, IVF_MAX_SCORES);
+    return IVF_OK;
+}
+
+// Dynamic LDS sizes of the stage kernels; raises the kernels' limits where they exceed the default window.
+struct LdsPlan { size_t scan, merge, sp; };
+
+int plan_lds(const ivf_index *ix, int P, int k, const SearchPlan &pl, LdsPlan &l)
+{
+    const int64_t PL = (int64_t)P * ix->L;
+    l.scan = (size_t)SCAN_WAVES * pool_capacity(k) * sizeof(uint64_t);   // dynamic part: the pools
+    l.merge = ((size_t)pl.merge_n + pl.merge_pow2) * sizeof(uint64_t);
+    l.sp = (size_t)(PL + 3 * P) * sizeof(uint32_t);
+    if (l.sp > 154 * 1024)   // one workgroup holds a query's scores in the 160 KB of LDS, beside 5 KB of static data
+        return fail(IVF_EINVAL, "nprobe*L + 3*nprobe = %lld words exceed the LDS of one workgroup", (long long)(PL + 3 * P));
+    if (l.sp > 48 * 1024) {
+        const void *fn = PL > 16384 ? reinterpret_cast<const void *>(&score_prune_kernel<1024, 8>)
+                         : PL > 4096 ? reinterpret_cast<const void *>(&score_prune_kernel<1024, 4>)
+                                     : reinterpret_cast<const void *>(&score_prune_kernel<256, 4>);
+        HIPCHK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l.sp));
+    }
+    if (l.merge > 40 * 1024)
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&merge_kernel<256>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)l.merge));
+    if (l.scan > 32 * 1024) {   // dynamic + static LDS above the default 64 KB window
+        const void *fn = ix->M == 16 ? reinterpret_cast<const void *>(&scan_kernel<16>)
+                                     : reinterpret_cast<const void *>(&scan_kernel<8>);
+        HIPCHK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l.scan));
+    }
+    return IVF_OK;
+}
+
+// The launch sequence of the query path over the batch, `pl.tile` queries per pass, on scratch the
+// caller provides.  Allocates nothing (stage timing, which creates events, is the allocating
+// entry points' option: `timed`).
+int run_search(ivf_index *ix, const SearchArgs &a, const SearchPlan &pl, const LdsPlan &lds, const SearchWs &ws,
+               bool timed, hipStream_t st)
+{
+    const int P = a.P, L = ix->L, M = ix->M, D = ix->D, S = a.S, k = a.k;
+    const int64_t K = ix->K, PL = (int64_t)P * L;
+    const int Dp = packed_dim(D);
+    int rc;
+    for (int64_t q0 = 0; q0 < a.nq; q0 += pl.tile) {
+        const int64_t n = (a.nq - q0 < pl.tile) ? a.nq - q0 : pl.tile;
+        const float *Q = a.queries + q0 * D;
+        int32_t *pid = a.probe_id_out ? a.probe_id_out + q0 * P : ws.probe_id;
+        float *pd = a.probe_d_out ? a.probe_d_out + q0 * P : ws.probe_d;
+
+        auto mark = [&](int stage) -> int {
+            if (!timed) return IVF_OK;
+            hipEvent_t e;
+            HIPCHK(hipEventCreate(&e));
+            HIPCHK(hipEventRecord(e, st));
+            ix->ev[stage].push_back(e);
+            return IVF_OK;
+        };
+        if ((rc = mark(0))) return rc;
+        if ((rc = pack_rows(Q, n, D, nullptr, ws.qpk, ws.qn, ws.qsi, st))) return rc;
+        if ((rc = launch_coarse(ws.qpk, ws.qn, ws.qsi, n, ix->cpk, ix->cnorm, ix->csi, K, Dp, ws.dt, ws.bm, st))) return rc;
+        if ((rc = mark(1))) return rc;
+        if ((rc = launch_probe_select(ws.dt, ws.bm, n, K, P, pid, pd, st))) return rc;
+        if ((rc = mark(2))) return rc;
+
+        int64_t *ks = a.kept_sub_out ? a.kept_sub_out + q0 * S : nullptr;
+        int64_t *ns = a.n_scanned_out ? a.n_scanned_out + q0 : nullptr;
+        if (PL > 16384)
+            score_prune_kernel<1024, 8><<<dim3((unsigned)n), dim3(1024), lds.sp, st>>>(
+                ws.dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, ws.desc, ks, ns);
+        else if (PL > 4096)
+            score_prune_kernel<1024, 4><<<dim3((unsigned)n), dim3(1024), lds.sp, st>>>(
+                ws.dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, ws.desc, ks, ns);
+        else
+            score_prune_kernel<256, 4><<<dim3((unsigned)n), dim3(256), lds.sp, st>>>(
+                ws.dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, ws.desc, ks, ns);
+        LAUNCHCHK("score_prune_kernel");
+        if ((rc = mark(3))) return rc;
+
+        lut_kernel<<<dim3((unsigned)n), dim3(256), (size_t)D * sizeof(float), st>>>(Q, D, M, ix->codebook, ws.lut);
+        LAUNCHCHK("lut_kernel");
+        if ((rc = mark(4))) return rc;
+
+        if (M == 16)
+            scan_kernel<16><<<dim3((unsigned)(n * pl.nsplit)), dim3(SCAN_BLOCK), lds.scan, st>>>(
+                ix->blocks, ix->const_table, ws.desc, S, ws.lut, k, pl.nsplit, ws.partial);
+        else
+            scan_kernel<8><<<dim3((unsigned)(n * pl.nsplit)), dim3(SCAN_BLOCK), lds.scan, st>>>(
+                ix->blocks, ix->const_table, ws.desc, S, ws.lut, k, pl.nsplit, ws.partial);
+        LAUNCHCHK("scan_kernel");
+        if ((rc = mark(5))) return rc;
+
+        merge_kernel<256><<<dim3((unsigned)n), dim3(256), lds.merge, st>>>(
+            ws.partial, ix->ids, pl.merge_n, pl.merge_pow2, k, a.out_ids + q0 * k, a.out_dists + q0 * k);
+        LAUNCHCHK("merge_kernel");
+        if ((rc = mark(6))) return rc;
+        if (timed) ix->launches++;
+    }
+    return IVF_OK;
+}
+
+// Scratch for callers that must not allocate: one array per GPU, part of the loaded code object,
+// so it exists from the moment the library is loaded until the process ends.  Host code never uses
+// the array's name as an address; it asks the runtime for the array's device address once per
+// device and keeps that.
+static __device__ __align__(256) unsigned char scratch[IVF_NOALLOC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+unsigned char *g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of this GPU's copy of `scratch` (the current device).
+int scratch_of_current_device(unsigned char **out)
+{
+    int dev = -1;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(IVF_EINVAL, "device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIPCHK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(IVF_EHIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = static_cast<unsigned char *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return IVF_OK;
+}
+
+}  // namespace
+
+extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq, int nprobe,
+                                 float prune_frac, int k, int32_t *out_ids, float *out_dists,
+                                 int32_t *probe_id_out, float *probe_d_out, int64_t *kept_sub_out,
+                                 int64_t *n_scanned_out, void *hip_stream)
+{
+    int rc = check_search_args(ix, queries, nq, nprobe, prune_frac, k, out_ids, out_dists);
+    if (rc || nq == 0) return rc;
     const int64_t K = ix->K;
-    const int64_t PL = (int64_t)P * L;
-    if (PL > 32000) return fail(IVF_EINVAL, "nprobe*L=%lld exceeds 32000", (long long)PL);
-    const int S = (int)ivf_num_kept(P, L, prune_frac);
+    const int S = (int)ivf_num_kept(nprobe, ix->L, prune_frac);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
     // queries per pass: bounded by the distance tile
@@ -355,112 +561,63 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
     else if (tile >= 256) tile -= tile % 256;   // whole blocks of the padded row count
     else if (tile >= GT) tile -= tile % GT;
 
-    // workgroups per query in the scan: fill the chip when the batch is small
-    int nsplit = (int)((2048 + tile - 1) / tile);
-    if (nsplit > 64) nsplit = 64;
-    if (nsplit > (S + 15) / 16) nsplit = (S + 15) / 16;
-    while (nsplit > 1 && (int64_t)nsplit * SCAN_WAVES * k > 8192) --nsplit;
-    if (nsplit < 1) nsplit = 1;
-    const int n_lists = nsplit * SCAN_WAVES;
-    const int merge_n = n_lists * k, merge_pow2 = next_pow2(merge_n);
+    const SearchPlan pl = plan_search(K, ix->D, ix->M, nprobe, S, k, tile);
+    Buf *bufs[WS_COUNT] = {&ix->dt, &ix->bm, &ix->qn, &ix->qsi, &ix->qpk, &ix->probe_id, &ix->probe_d,
+                           &ix->desc, &ix->lut, &ix->partial};
+    for (int i = 0; i < WS_COUNT; ++i)
+        if ((rc = ensure(*bufs[i], pl.bytes[i]))) return rc;
+    SearchWs ws;
+    ws.dt = static_cast<float *>(ix->dt.p);
+    ws.bm = static_cast<float *>(ix->bm.p);
+    ws.qn = static_cast<float *>(ix->qn.p);
+    ws.qsi = static_cast<float *>(ix->qsi.p);
+    ws.qpk = static_cast<_Float16 *>(ix->qpk.p);
+    ws.probe_id = static_cast<int32_t *>(ix->probe_id.p);
+    ws.probe_d = static_cast<float *>(ix->probe_d.p);
+    ws.desc = static_cast<SubDesc *>(ix->desc.p);
+    ws.lut = static_cast<float *>(ix->lut.p);
+    ws.partial = static_cast<uint64_t *>(ix->partial.p);
+    LdsPlan lds;
+    if ((rc = plan_lds(ix, nprobe, k, pl, lds))) return rc;
+    const SearchArgs a = {queries, nq, nprobe, k, S, out_ids, out_dists, probe_id_out, probe_d_out, kept_sub_out,
+                          n_scanned_out};
+    return run_search(ix, a, pl, lds, ws, ix->profile, st);
+}
 
-    int rc;
-    const size_t tile_pad = (size_t)packed_rows(tile);   // the GEMM may write whole tiles of rows
-    if ((rc = ensure(ix->dt, tile_pad * dt_stride(K) * sizeof(float)))) return rc;
-    const int64_t nb = (K + BMW - 1) / BMW;
-    if ((rc = ensure(ix->bm, tile_pad * nb * sizeof(float)))) return rc;
-    if ((rc = ensure(ix->qn, tile_pad * sizeof(float)))) return rc;
-    const int Dp = packed_dim(D);
-    if ((rc = ensure(ix->qpk, (size_t)packed_rows(tile) * Dp * 2 * sizeof(_Float16)))) return rc;
-    if ((rc = ensure(ix->qsi, tile_pad * sizeof(float)))) return rc;
-    if ((rc = ensure(ix->probe_id, (size_t)tile * P * sizeof(int32_t)))) return rc;
-    if ((rc = ensure(ix->probe_d, (size_t)tile * P * sizeof(float)))) return rc;
-    if ((rc = ensure(ix->desc, (size_t)tile * S * sizeof(SubDesc)))) return rc;
-    if ((rc = ensure(ix->lut, (size_t)tile * M * 256 * sizeof(float)))) return rc;
-    if ((rc = ensure(ix->partial, (size_t)tile * merge_n * sizeof(uint64_t)))) return rc;
-
-    const size_t scan_lds = (size_t)SCAN_WAVES * pool_capacity(k) * sizeof(uint64_t);   // dynamic part: the pools
-    const size_t merge_lds = ((size_t)merge_n + merge_pow2) * sizeof(uint64_t);
-    const size_t sp_lds = (size_t)(PL + 3 * P) * sizeof(uint32_t);
-    if (sp_lds > 128 * 1024) return fail(IVF_EINVAL, "nprobe*L=%lld exceeds the 32768 scores one workgroup holds", (long long)PL);
-    if (sp_lds > 48 * 1024) {
-        const void *fn = PL > 16384 ? reinterpret_cast<const void *>(&score_prune_kernel<1024, 8>)
-                         : PL > 4096 ? reinterpret_cast<const void *>(&score_prune_kernel<1024, 4>)
-                                     : reinterpret_cast<const void *>(&score_prune_kernel<256, 4>);
-        HIPCHK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sp_lds));
+extern "C" int ivf_search_noalloc(ivf_index *ix, const float *queries, int64_t nq, int nprobe, float prune_frac,
+                                  int k, int32_t *out_ids, float *out_dists, void *hip_stream)
+{
+    int rc = check_search_args(ix, queries, nq, nprobe, prune_frac, k, out_ids, out_dists);
+    if (rc || nq == 0) return rc;
+    const int S = (int)ivf_num_kept(nprobe, ix->L, prune_frac);
+    // the whole batch in one pass: the scratch is carved out of the static array, 256-byte aligned pieces
+    const SearchPlan pl = plan_search(ix->K, ix->D, ix->M, nprobe, S, k, nq);
+    size_t off[WS_COUNT], total = 0;
+    for (int i = 0; i < WS_COUNT; ++i) {
+        off[i] = total;
+        total += (pl.bytes[i] + 255) / 256 * 256;
     }
-    if (merge_lds > 40 * 1024)
-        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&merge_kernel<256>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_lds));
-    if (scan_lds > 32 * 1024) {   // dynamic + static LDS above the default 64 KB window
-        const void *fn = M == 16 ? reinterpret_cast<const void *>(&scan_kernel<16>)
-                                 : reinterpret_cast<const void *>(&scan_kernel<8>);
-        HIPCHK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds));
-    }
-
-    for (int64_t q0 = 0; q0 < nq; q0 += tile) {
-        const int64_t n = (nq - q0 < tile) ? nq - q0 : tile;
-        const float *Q = queries + q0 * D;
-        float *Dt = static_cast<float *>(ix->dt.p);
-        float *qn = static_cast<float *>(ix->qn.p);
-        float *bm = static_cast<float *>(ix->bm.p);
-        int32_t *pid = probe_id_out ? probe_id_out + q0 * P : static_cast<int32_t *>(ix->probe_id.p);
-        float *pd = probe_d_out ? probe_d_out + q0 * P : static_cast<float *>(ix->probe_d.p);
-        SubDesc *desc = static_cast<SubDesc *>(ix->desc.p);
-        float *lut = static_cast<float *>(ix->lut.p);
-        uint64_t *partial = static_cast<uint64_t *>(ix->partial.p);
-
-        auto mark = [&](int stage) -> int {
-            if (!ix->profile) return IVF_OK;
-            hipEvent_t e;
-            HIPCHK(hipEventCreate(&e));
-            HIPCHK(hipEventRecord(e, st));
-            ix->ev[stage].push_back(e);
-            return IVF_OK;
-        };
-        if ((rc = mark(0))) return rc;
-        _Float16 *qpk = static_cast<_Float16 *>(ix->qpk.p);
-        float *qsi = static_cast<float *>(ix->qsi.p);
-        if ((rc = pack_rows(Q, n, D, nullptr, qpk, qn, qsi, st))) return rc;
-        if ((rc = launch_coarse(qpk, qn, qsi, n, ix->cpk, ix->cnorm, ix->csi, K, Dp, Dt, bm, st))) return rc;
-        if ((rc = mark(1))) return rc;
-        if ((rc = launch_probe_select(Dt, bm, n, K, P, pid, pd, st))) return rc;
-        if ((rc = mark(2))) return rc;
-
-        int64_t *ks = kept_sub_out ? kept_sub_out + q0 * S : nullptr;
-        int64_t *ns = n_scanned_out ? n_scanned_out + q0 : nullptr;
-        if (PL > 16384)
-            score_prune_kernel<1024, 8><<<dim3((unsigned)n), dim3(1024), sp_lds, st>>>(
-                Dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, desc, ks, ns);
-        else if (PL > 4096)
-            score_prune_kernel<1024, 4><<<dim3((unsigned)n), dim3(1024), sp_lds, st>>>(
-                Dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, desc, ks, ns);
-        else
-            score_prune_kernel<256, 4><<<dim3((unsigned)n), dim3(256), sp_lds, st>>>(
-                Dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, desc, ks, ns);
-        LAUNCHCHK("score_prune_kernel");
-        if ((rc = mark(3))) return rc;
-
-        lut_kernel<<<dim3((unsigned)n), dim3(256), (size_t)D * sizeof(float), st>>>(Q, D, M, ix->codebook, lut);
-        LAUNCHCHK("lut_kernel");
-        if ((rc = mark(4))) return rc;
-
-        if (M == 16)
-            scan_kernel<16><<<dim3((unsigned)(n * nsplit)), dim3(SCAN_BLOCK), scan_lds, st>>>(
-                ix->blocks, ix->const_table, desc, S, lut, k, nsplit, partial);
-        else
-            scan_kernel<8><<<dim3((unsigned)(n * nsplit)), dim3(SCAN_BLOCK), scan_lds, st>>>(
-                ix->blocks, ix->const_table, desc, S, lut, k, nsplit, partial);
-        LAUNCHCHK("scan_kernel");
-        if ((rc = mark(5))) return rc;
-
-        merge_kernel<256><<<dim3((unsigned)n), dim3(256), merge_lds, st>>>(
-            partial, ix->ids, merge_n, merge_pow2, k, out_ids + q0 * k, out_dists + q0 * k);
-        LAUNCHCHK("merge_kernel");
-        if ((rc = mark(6))) return rc;
-        if (ix->profile) ix->launches++;
-    }
-    return IVF_OK;
+    if (total > (size_t)IVF_NOALLOC_SCRATCH_BYTES)
+        return fail(IVF_EINVAL, "ivf_search_noalloc: this batch needs %zu bytes of scratch, the static array holds %zu "
+                    "(nq=%lld, K=%lld); use fewer queries per call or ivf_search",
+                    total, (size_t)IVF_NOALLOC_SCRATCH_BYTES, (long long)nq, (long long)ix->K);
+    unsigned char *base = nullptr;
+    if ((rc = scratch_of_current_device(&base))) return rc;
+    SearchWs ws;
+    ws.dt = reinterpret_cast<float *>(base + off[WS_DT]);
+    ws.bm = reinterpret_cast<float *>(base + off[WS_BM]);
+    ws.qn = reinterpret_cast<float *>(base + off[WS_QN]);
+    ws.qsi = reinterpret_cast<float *>(base + off[WS_QSI]);
+    ws.qpk = reinterpret_cast<_Float16 *>(base + off[WS_QPK]);
+    ws.probe_id = reinterpret_cast<int32_t *>(base + off[WS_PID]);
+    ws.probe_d = reinterpret_cast<float *>(base + off[WS_PD]);
+    ws.desc = reinterpret_cast<SubDesc *>(base + off[WS_DESC]);
+    ws.lut = reinterpret_cast<float *>(base + off[WS_LUT]);
+    ws.partial = reinterpret_cast<uint64_t *>(base + off[WS_PARTIAL]);
+    LdsPlan lds;
+    if ((rc = plan_lds(ix, nprobe, k, pl, lds))) return rc;
+    const SearchArgs a = {queries, nq, nprobe, k, S, out_ids, out_dists, nullptr, nullptr, nullptr, nullptr};
+    return run_search(ix, a, pl, lds, ws, false, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" int ivf_profile_enable(ivf_index *ix, int on)
