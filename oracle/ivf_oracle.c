@@ -184,13 +184,42 @@ void orc_lut(const float *Q, int64_t nq, int D, int M, const float *codebook, do
 
 /* --------------------------------------------- stage 5: ADC scan ----------- */
 
-/* Number of stored points in the kept subregions of each query. */
-void orc_scan_count(const int64_t *kept_sub, int64_t nq, int64_t S, const uint32_t *sub_offsets,
-                    int64_t *count)
+/* Candidate budget (Section 4 evaluates candidate lists of a given length R).
+ * The kept subregions of a query are visited in ascending order of their
+ * Eq. (7) distance, ties by subregion id, and the traversal stops as soon as
+ * the points collected so far number R or more: a subregion is visited iff
+ * the subregions before it in that order hold fewer than R points together
+ * (the one that crosses R is taken whole; empty ones on the way count as
+ * visited).  kept_sub / kept_score are [nq][S] in any order; visit[q][j] = 1
+ * if kept_sub[q][j] is visited, else 0. */
+void orc_budget_visit(const int64_t *kept_sub, const double *kept_score, int64_t nq, int64_t S,
+                      const uint32_t *sub_offsets, int64_t R, uint8_t *visit)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t q = 0; q < nq; ++q) {
+        int64_t *order = (int64_t *)malloc((size_t)S * sizeof(int64_t));
+        double *val = (double *)malloc((size_t)S * sizeof(double));
+        orc_smallest(kept_score + q * S, kept_sub + q * S, S, S, order, val);
+        int64_t collected = 0;
+        for (int64_t j = 0; j < S; ++j) {
+            int64_t at = order[j], b = kept_sub[q * S + at];
+            visit[q * S + at] = collected < R ? 1 : 0;
+            if (collected < R) collected += (int64_t)sub_offsets[b + 1] - (int64_t)sub_offsets[b];
+        }
+        free(order);
+        free(val);
+    }
+}
+
+/* Number of stored points in the kept (and, if visit is given, visited)
+ * subregions of each query. */
+void orc_scan_count(const int64_t *kept_sub, const uint8_t *visit, int64_t nq, int64_t S,
+                    const uint32_t *sub_offsets, int64_t *count)
 {
     for (int64_t q = 0; q < nq; ++q) {
         int64_t c = 0;
         for (int64_t j = 0; j < S; ++j) {
+            if (visit && !visit[q * S + j]) continue;
             int64_t b = kept_sub[q * S + j];
             c += (int64_t)sub_offsets[b + 1] - (int64_t)sub_offsets[b];
         }
@@ -203,8 +232,9 @@ void orc_scan_count(const int64_t *kept_sub, int64_t nq, int64_t S, const uint32
  * where const is const_table[const_byte[i]], or const_exact[i] when that
  * array is given (the unquantised per-point term, used to pin the identity).
  * Candidates of query q are written from cand_start[q] on, in the order of
- * kept_sub and then of position. */
-void orc_scan(const int64_t *kept_sub, const double *kept_score, int64_t nq, int64_t S,
+ * kept_sub and then of position.  With visit given, subregions whose flag is
+ * 0 are skipped (candidate budget). */
+void orc_scan(const int64_t *kept_sub, const double *kept_score, const uint8_t *visit, int64_t nq, int64_t S,
               const uint32_t *sub_offsets, const uint8_t *codes, int M, const uint8_t *const_byte,
               const float *const_table, const double *const_exact, const double *T,
               const int64_t *cand_start, int64_t *cand_pos, double *cand_dist)
@@ -213,6 +243,7 @@ void orc_scan(const int64_t *kept_sub, const double *kept_score, int64_t nq, int
     for (int64_t q = 0; q < nq; ++q) {
         int64_t w = cand_start[q];
         for (int64_t j = 0; j < S; ++j) {
+            if (visit && !visit[q * S + j]) continue;
             int64_t b = kept_sub[q * S + j];
             for (int64_t i = sub_offsets[b]; i < (int64_t)sub_offsets[b + 1]; ++i) {
                 double d = kept_score[q * S + j];
@@ -285,10 +316,10 @@ void orc_search(const orc_index *ix, const float *Q, int64_t nq, int64_t P, doub
         orc_scores(qv, 1, ix->centroids, D, ix->nbr, L, ix->alpha, ix->cs_dist2, probe_id, P, scores);
         orc_prune(scores, 1, P, L, probe_id, S, kept_sub, kept_score);
         orc_lut(qv, 1, D, M, ix->pq_codebook, T);
-        orc_scan_count(kept_sub, 1, S, ix->sub_offsets, &count);
+        orc_scan_count(kept_sub, NULL, 1, S, ix->sub_offsets, &count);
         int64_t *cand_pos = (int64_t *)malloc((size_t)(count > 0 ? count : 1) * sizeof(int64_t));
         double *cand_dist = (double *)malloc((size_t)(count > 0 ? count : 1) * sizeof(double));
-        orc_scan(kept_sub, kept_score, 1, S, ix->sub_offsets, ix->codes, M, ix->const_byte,
+        orc_scan(kept_sub, kept_score, NULL, 1, S, ix->sub_offsets, ix->codes, M, ix->const_byte,
                  ix->const_table, NULL, T, &zero, cand_pos, cand_dist);
         orc_select(cand_pos, cand_dist, count, ix->ids, k, out_ids + q * k, out_dists + q * k);
         if (n_scanned) n_scanned[q] = count;

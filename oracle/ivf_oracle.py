@@ -136,19 +136,29 @@ def lut(Q, ix):
     return T
 
 
-def scan(ix, kept_sub, kept_score, T, const_exact=None):
+def budget_visit(ix, kept_sub, kept_score, R):
+    """Candidate budget: flags [nq, S] of the kept subregions that are visited before R points are collected."""
+    kept_sub, kept_score = _i64(kept_sub), _f64(kept_score)
+    nq, S = kept_sub.shape
+    visit = np.empty((nq, S), np.uint8)
+    lib().orc_budget_visit(_p(kept_sub), _p(kept_score), I64(nq), I64(S), _p(ix.sub_offsets), I64(R), _p(visit))
+    return visit
+
+
+def scan(ix, kept_sub, kept_score, T, const_exact=None, visit=None):
     """Candidates of every query: (start offsets [nq+1], positions, distances)."""
     kept_sub, kept_score, T = _i64(kept_sub), _f64(kept_score), _f64(T)
     nq, S = kept_sub.shape
     cnt = np.empty(nq, np.int64)
-    lib().orc_scan_count(_p(kept_sub), I64(nq), I64(S), _p(ix.sub_offsets), _p(cnt))
+    vis = None if visit is None else _u8(visit)
+    lib().orc_scan_count(_p(kept_sub), _p(vis), I64(nq), I64(S), _p(ix.sub_offsets), _p(cnt))
     start = np.zeros(nq + 1, np.int64)
     np.cumsum(cnt, out=start[1:])
     tot = int(start[-1])
     pos = np.empty(max(tot, 1), np.int64)
     dist = np.empty(max(tot, 1), np.float64)
     ce = None if const_exact is None else _f64(const_exact)
-    lib().orc_scan(_p(kept_sub), _p(kept_score), I64(nq), I64(S), _p(ix.sub_offsets), _p(ix.codes),
+    lib().orc_scan(_p(kept_sub), _p(kept_score), _p(vis), I64(nq), I64(S), _p(ix.sub_offsets), _p(ix.codes),
                    INT(ix.M), _p(ix.const_byte), _p(ix.const_table), _p(ce), _p(T), _p(start),
                    _p(pos), _p(dist))
     return start, pos[:tot], dist[:tot]
@@ -185,12 +195,20 @@ def search(ix, Q, nprobe, prune_frac, k):
     return oi, od, ns
 
 
-def search_staged(ix, Q, nprobe, prune_frac, k, probe_id=None, kept=None):
+def search_budget(ix, Q, nprobe, prune_frac, R, k):
+    """Whole query path with a candidate budget R: (ids, dists, codes scanned [nq], staged intermediates)."""
+    st = search_staged(ix, Q, nprobe, prune_frac, k, budget=R)
+    return st["ids"], st["dists"], np.diff(st["cand_start"]), st
+
+
+def search_staged(ix, Q, nprobe, prune_frac, k, probe_id=None, kept=None, budget=None, visit=None):
     """Stages 1-6 one after another, returning every intermediate.
 
     ``probe_id`` ([nq, P]) or ``kept`` ([nq, S] subregion ids) replace the
     oracle's own selection of that stage (used to carry on after a reported
-    near-tie); all values are still recomputed here in fp64.
+    near-tie); all values are still recomputed here in fp64.  ``budget`` = R
+    switches the candidate budget on (``out["visit"]`` are the flags of the
+    subregions in ``out["scan_sub"]``); ``visit`` replaces the oracle's flags.
     """
     Q = _f32(Q)
     out = {}
@@ -214,7 +232,14 @@ def search_staged(ix, Q, nprobe, prune_frac, k, probe_id=None, kept=None):
             kscore[q] = sc[q].ravel()[where]
     T = lut(Q, ix)
     out["lut"] = T
-    start, cpos, cdist = scan(ix, ksub, kscore, T)
+    out["scan_sub"], out["scan_score"] = ksub, kscore
+    vis = None
+    if budget is not None:
+        vis = budget_visit(ix, ksub, kscore, budget)
+        out["visit"] = vis
+        if visit is not None:
+            vis = _u8(visit)
+    start, cpos, cdist = scan(ix, ksub, kscore, T, visit=vis)
     out["cand_start"], out["cand_pos"], out["cand_dist"] = start, cpos, cdist
     oi = np.empty((Q.shape[0], k), np.int32)
     od = np.empty((Q.shape[0], k), np.float64)

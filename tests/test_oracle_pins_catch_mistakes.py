@@ -82,6 +82,18 @@ MUTATIONS = {
         "            double d = fabs(t[i] - (double)table[j]);\n            if (d < best) { best = d; bj = j; }",
         "            double d = fabs(t[i] - (double)table[j]);\n            if (d <= best) { best = d; bj = j; }",
         ["test_scalar_quantiser"]),
+    "budget_stops_before_crossing": (
+        "visit[q * S + at] = collected < R ? 1 : 0;\n            if (collected < R) collected += (int64_t)sub_offsets[b + 1] - (int64_t)sub_offsets[b];",
+        "collected += (int64_t)sub_offsets[b + 1] - (int64_t)sub_offsets[b];\n            visit[q * S + at] = collected <= R ? 1 : 0;",
+        ["test_budget_walk_against_python_traversal"]),
+    "budget_order_by_position": (
+        "orc_smallest(kept_score + q * S, kept_sub + q * S, S, S, order, val);",
+        "orc_smallest(kept_score + q * S, NULL, S, S, order, val);",
+        ["test_budget_walk_against_python_traversal"]),
+    "budget_counts_subregions": (
+        "if (collected < R) collected += (int64_t)sub_offsets[b + 1] - (int64_t)sub_offsets[b];",
+        "if (collected < R) collected += 1;",
+        ["test_budget_walk_against_python_traversal", "test_budget_nested_and_unbounded_budget_is_plain_search"]),
     "subcentroid_weights": (
         "double mu = (double)c[t] + a * ((double)s[t] - (double)c[t]);",
         "double mu = (double)c[t] + (1.0 - a) * ((double)s[t] - (double)c[t]);",

@@ -276,3 +276,67 @@ def test_recall_against_exact_knn_grows_with_nprobe(tiny):
     assert all(b >= a for a, b in zip(nn_in_cands, nn_in_cands[1:]))     # nested candidate sets: exact
     assert all(b >= a - 0.02 for a, b in zip(recalls, recalls[1:]))      # reranked by compressed distances: trend
     assert nn_in_cands[-1] >= 0.95 and recalls[-1] >= recalls[0]
+
+
+# ---------------------------------------------------------- candidate budget
+
+
+def _walk(sub, score, sizes, R):
+    """The traversal written out: ascending (score, subregion id), stop once R points are in."""
+    order = sorted(range(len(sub)), key=lambda j: (score[j], sub[j]))
+    flags, collected = [0] * len(sub), 0
+    for j in order:
+        if collected >= R:
+            break
+        flags[j] = 1
+        collected += sizes[sub[j]]
+    return flags, collected
+
+
+def test_budget_walk_against_python_traversal(rng):
+    """Planted ties in the scores, empty subregions, budgets below, at and above what is there."""
+    nsub, nq, S = 40, 5, 17
+    sizes = rng.integers(0, 6, nsub)
+    sizes[rng.permutation(nsub)[:8]] = 0
+    off = np.zeros(nsub + 1, np.uint32)
+    off[1:] = np.cumsum(sizes)
+    ix = tiny_index(K=nsub, L=1, sub_offsets=off, codes=np.zeros((int(off[-1]), 1), np.uint8),
+                    const_byte=np.zeros(int(off[-1]), np.uint8), ids=np.arange(int(off[-1]), dtype=np.int32))
+    sub = np.stack([rng.permutation(nsub)[:S] for _ in range(nq)]).astype(np.int64)
+    score = rng.integers(0, 5, (nq, S)).astype(np.float64)
+    for R in (1, 2, 7, 20, 10 ** 6):
+        vis = orc.budget_visit(ix, sub, score, R)
+        for q in range(nq):
+            flags, collected = _walk(sub[q].tolist(), score[q].tolist(), sizes, R)
+            assert vis[q].tolist() == flags, (R, q)
+            total = int(sizes[sub[q]].sum())
+            got = int(sizes[sub[q]][vis[q] == 1].sum())
+            assert got == collected and got >= min(R, total)
+            if got > R:                                   # only the subregion that crosses R overshoots
+                last = max((j for j in range(S) if flags[j]), key=lambda j: (score[q, j], sub[q, j]))
+                assert got - sizes[sub[q, last]] < R
+
+
+def test_budget_nested_and_unbounded_budget_is_plain_search(tiny):
+    spec, ix, Q, X = tiny
+    Qs = Q[:12]
+    ids_all, d_all, ns_all = orc.search(ix, Qs, spec.nprobe, 0.5, 10)
+    ids_b, d_b, ns_b, st = orc.search_budget(ix, Qs, spec.nprobe, 0.5, 10 ** 9, 10)
+    assert (ids_b == ids_all).all() and (d_b == d_all).all() and (ns_b == ns_all).all()
+    assert (st["visit"] == 1).all()
+    prev = None
+    for R in (1, 50, 300, 1000):
+        ids_r, d_r, ns_r, st = orc.search_budget(ix, Qs, spec.nprobe, 0.5, R, 10)
+        assert (ns_r >= np.minimum(R, ns_all)).all() and (ns_r <= ns_all).all()
+        if prev is not None:
+            assert (st["visit"] >= prev).all()            # a larger budget visits a superset
+        prev = st["visit"]
+        # the result is the plain top-k over exactly the visited subregions' points
+        for q in range(len(Qs)):
+            cp = st["cand_pos"][st["cand_start"][q]:st["cand_start"][q + 1]]
+            cd = st["cand_dist"][st["cand_start"][q]:st["cand_start"][q + 1]]
+            sizes = np.diff(ix.sub_offsets.astype(np.int64))[st["scan_sub"][q]]
+            assert len(cp) == int(sizes[st["visit"][q] == 1].sum())
+            ref = sorted(zip(cd.tolist(), ix.ids[cp].tolist()))[:10]
+            got = [(d, i) for d, i in zip(d_r[q].tolist(), ids_r[q].tolist()) if i >= 0]
+            assert got == ref
