@@ -158,6 +158,25 @@ int ivf_search_stages(ivf_index *index, const float *queries, int64_t nq, int np
                       int32_t *probe_id, float *probe_d, int64_t *kept_sub, int64_t *n_scanned,
                       void *hip_stream);
 
+/*
+ * Search with a candidate budget (Section 4 evaluates the system at a given
+ * candidate-list length R, e.g. 30 000): stages 1-3 as in ivf_search, then the
+ * kept subregions are visited in ascending order of their Eq. (7) distance,
+ * ties by subregion id, and the traversal stops as soon as the points
+ * collected so far number max_candidates or more; the subregion with which
+ * that number is reached is scanned whole, empty subregions on the way count
+ * as visited.  Stages 4-6 then run over the visited subregions only.
+ * max_candidates >= 1; a budget larger than what the kept subregions hold
+ * gives ivf_search's result.  Optional outputs (any may be NULL):
+ *   kept_sub  [nq][S] int64  the kept subregion ids, ascending (stage 3)
+ *   visited   [nq][S] uint8  1 where kept_sub[q][i] was visited, else 0
+ *   n_scanned [nq]    int64  point records read (the candidate-list length)
+ * Other arguments, limits, stream and scratch behaviour as for ivf_search.
+ */
+int ivf_search_budget(ivf_index *index, const float *queries, int64_t nq, int nprobe, float prune_frac,
+                      int64_t max_candidates, int k, int32_t *out_ids, float *out_dists,
+                      int64_t *kept_sub, uint8_t *visited, int64_t *n_scanned, void *hip_stream);
+
 /* S of stage 3 for the given parameters (host call, no device work). */
 int64_t ivf_num_kept(int nprobe, int L, float prune_frac);
 

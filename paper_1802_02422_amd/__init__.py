@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     ivf_search,
     ivf_search_stages,
     ivf_search_noalloc,
+    ivf_search_budget,
     ivf_num_kept,
     ivf_coarse_topk,
     ivf_encode,

@@ -51,6 +51,7 @@ def load_library():
     lib.ivf_set_scratch_limit.argtypes = [vp, i64]
     lib.ivf_search.argtypes = [vp, vp, i64, i32, f32, i32, vp, vp, vp]
     lib.ivf_search_noalloc.argtypes = [vp, vp, i64, i32, f32, i32, vp, vp, vp]
+    lib.ivf_search_budget.argtypes = [vp, vp, i64, i32, f32, i64, i32, vp, vp, vp, vp, vp, vp]
     lib.ivf_search_stages.argtypes = [vp, vp, i64, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.ivf_num_kept.argtypes = [i32, i32, f32]
     lib.ivf_num_kept.restype = i64
@@ -215,6 +216,27 @@ def ivf_search_stages(index: IndexHandle, queries: torch.Tensor, nprobe: int, pr
         index.ptr, _ptr(queries), nq, nprobe, prune_frac, k, _ptr(out["ids"]), _ptr(out["dists"]),
         _ptr(out["probe_id"]), _ptr(out["probe_d"]), _ptr(out["kept_sub"]), _ptr(out["n_scanned"]),
         _stream()))
+    return out
+
+
+def ivf_search_budget(index: IndexHandle, queries: torch.Tensor, nprobe: int, prune_frac: float,
+                      max_candidates: int, k: int):
+    """Search that stops collecting candidates after ``max_candidates`` points: ids, dists, the kept
+    subregions, the flags of the visited ones and the number of records read per query."""
+    nq = queries.shape[0]
+    _dev(queries, torch.float32, "queries", (nq, index.D))
+    dev = queries.device
+    S = ivf_num_kept(nprobe, index.L, prune_frac)
+    out = {
+        "ids": torch.empty((nq, k), dtype=torch.int32, device=dev),
+        "dists": torch.empty((nq, k), dtype=torch.float32, device=dev),
+        "kept_sub": torch.empty((nq, S), dtype=torch.int64, device=dev),
+        "visited": torch.empty((nq, S), dtype=torch.uint8, device=dev),
+        "n_scanned": torch.empty((nq,), dtype=torch.int64, device=dev),
+    }
+    _check(load_library().ivf_search_budget(
+        index.ptr, _ptr(queries), nq, nprobe, prune_frac, max_candidates, k, _ptr(out["ids"]), _ptr(out["dists"]),
+        _ptr(out["kept_sub"]), _ptr(out["visited"]), _ptr(out["n_scanned"]), _stream()))
     return out
 
 

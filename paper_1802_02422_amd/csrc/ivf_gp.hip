@@ -14,6 +14,7 @@
 #include <hip/hip_runtime.h>
 #include <rocprim/device/device_scan.hpp>
 
+#include "budget.hpp"
 #include "coarse.hpp"
 #include "encode.hpp"
 #include "layout.hpp"
@@ -400,6 +401,8 @@ struct SearchArgs {
     float *probe_d_out;
     int64_t *kept_sub_out;
     int64_t *n_scanned_out;
+    int64_t budget;          // candidate budget R, 0 = none
+    uint8_t *visited_out;    // [nq][S] flags of the budget mode (may be NULL)
 };
 
 int check_search_args(const ivf_index *ix, const float *queries, int64_t nq, int nprobe, float prune_frac, int k,
@@ -490,6 +493,12 @@ int run_search(ivf_index *ix, const SearchArgs &a, const SearchPlan &pl, const L
             score_prune_kernel<256, 4><<<dim3((unsigned)n), dim3(256), lds.sp, st>>>(
                 ws.dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, ws.desc, ks, ns);
         LAUNCHCHK("score_prune_kernel");
+        if (a.budget > 0) {
+            const uint32_t R = a.budget > 0xFFFFFFFFll ? 0xFFFFFFFFu : (uint32_t)a.budget;
+            budget_cut_kernel<256><<<dim3((unsigned)n), dim3(256), 0, st>>>(
+                ws.desc, S, R, a.visited_out ? a.visited_out + q0 * S : nullptr, ns);
+            LAUNCHCHK("budget_cut_kernel");
+        }
         if ((rc = mark(3))) return rc;
 
         lut_kernel<<<dim3((unsigned)n), dim3(256), (size_t)D * sizeof(float), st>>>(Q, D, M, ix->codebook, ws.lut);
@@ -541,12 +550,11 @@ int scratch_of_current_device(unsigned char **out)
     return IVF_OK;
 }
 
-}  // namespace
-
-extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq, int nprobe,
-                                 float prune_frac, int k, int32_t *out_ids, float *out_dists,
-                                 int32_t *probe_id_out, float *probe_d_out, int64_t *kept_sub_out,
-                                 int64_t *n_scanned_out, void *hip_stream)
+// The query path on the handle's own growable scratch (allocates when a call needs more than any before).
+int search_alloc(ivf_index *ix, const float *queries, int64_t nq, int nprobe, float prune_frac, int k,
+                 int32_t *out_ids, float *out_dists, int32_t *probe_id_out, float *probe_d_out,
+                 int64_t *kept_sub_out, int64_t *n_scanned_out, int64_t budget, uint8_t *visited_out,
+                 void *hip_stream)
 {
     int rc = check_search_args(ix, queries, nq, nprobe, prune_frac, k, out_ids, out_dists);
     if (rc || nq == 0) return rc;
@@ -580,8 +588,29 @@ extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq
     LdsPlan lds;
     if ((rc = plan_lds(ix, nprobe, k, pl, lds))) return rc;
     const SearchArgs a = {queries, nq, nprobe, k, S, out_ids, out_dists, probe_id_out, probe_d_out, kept_sub_out,
-                          n_scanned_out};
+                          n_scanned_out, budget, visited_out};
     return run_search(ix, a, pl, lds, ws, ix->profile, st);
+}
+
+}  // namespace
+
+extern "C" int ivf_search_stages(ivf_index *ix, const float *queries, int64_t nq, int nprobe,
+                                 float prune_frac, int k, int32_t *out_ids, float *out_dists,
+                                 int32_t *probe_id_out, float *probe_d_out, int64_t *kept_sub_out,
+                                 int64_t *n_scanned_out, void *hip_stream)
+{
+    return search_alloc(ix, queries, nq, nprobe, prune_frac, k, out_ids, out_dists, probe_id_out, probe_d_out,
+                        kept_sub_out, n_scanned_out, 0, nullptr, hip_stream);
+}
+
+extern "C" int ivf_search_budget(ivf_index *ix, const float *queries, int64_t nq, int nprobe, float prune_frac,
+                                 int64_t max_candidates, int k, int32_t *out_ids, float *out_dists,
+                                 int64_t *kept_sub_out, uint8_t *visited_out, int64_t *n_scanned_out,
+                                 void *hip_stream)
+{
+    if (max_candidates < 1) return fail(IVF_EINVAL, "max_candidates=%lld must be positive", (long long)max_candidates);
+    return search_alloc(ix, queries, nq, nprobe, prune_frac, k, out_ids, out_dists, nullptr, nullptr,
+                        kept_sub_out, n_scanned_out, max_candidates, visited_out, hip_stream);
 }
 
 extern "C" int ivf_search_noalloc(ivf_index *ix, const float *queries, int64_t nq, int nprobe, float prune_frac,
@@ -616,7 +645,7 @@ extern "C" int ivf_search_noalloc(ivf_index *ix, const float *queries, int64_t n
     ws.partial = reinterpret_cast<uint64_t *>(base + off[WS_PARTIAL]);
     LdsPlan lds;
     if ((rc = plan_lds(ix, nprobe, k, pl, lds))) return rc;
-    const SearchArgs a = {queries, nq, nprobe, k, S, out_ids, out_dists, nullptr, nullptr, nullptr, nullptr};
+    const SearchArgs a = {queries, nq, nprobe, k, S, out_ids, out_dists, nullptr, nullptr, nullptr, nullptr, 0, nullptr};
     return run_search(ix, a, pl, lds, ws, false, static_cast<hipStream_t>(hip_stream));
 }
 
