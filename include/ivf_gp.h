@@ -211,16 +211,98 @@ int ivf_encode(const ivf_index_desc *trained, const float *x, int64_t n, const i
                float *out_const_t, float *out_residual, void *hip_stream);
 
 /*
- * Training statistics for alpha (Section 3.2, Eqs. (11)-(12)): for each of the
- * n training points x [n][D] with region[n], pick the neighbour s_l whose
- * line through c leaves the smallest residual with the coefficient clamped to
- * [0,1] (Eq. (10)-(11)), and accumulate num[r] += (x-c)^T(s_l-c),
- * den[r] += ||s_l-c||^2 into the caller's zero-initialised fp64 arrays
- * num[K], den[K]; alpha_r = num[r]/den[r] (Eq. (12)) is left to the caller.
+ * ---- Index construction on the device (Section 3.2 "The model" and "Learning
+ * the scaling factor"; Section 2 for the PQ codebooks).  Each routine waits
+ * for the stream before it returns, allocates and frees its own scratch, and
+ * is deterministic: no floating-point atomics, every sum is taken in an order
+ * fixed by the data layout, so the same inputs give the same bits.
+ */
+
+/*
+ * Lloyd's k-means for the region codebook (Section 2, IVFADC; Section 3.1 for
+ * codebooks of up to 2^20 centroids): centroids start as the rows
+ * init_idx[0..K) (device, int64) of x [n][D]; each of the `iters` rounds
+ * assigns every row to its nearest centroid by (distance, id) (the fused
+ * stage-1 kernel) and replaces every non-empty cluster's centroid by the mean
+ * of its rows, accumulated in fp64 and rounded to fp32; an empty cluster
+ * keeps its centroid.  centroids [K][D] (16-byte aligned) receives the result;
+ * objective (device, [iters] fp64, may be NULL) the sum of squared distances
+ * of each round's assignment, measured before that round's update.
+ */
+int ivf_kmeans(const float *x, int64_t n, int D, int64_t K, int iters, const int64_t *init_idx,
+               float *centroids, double *objective, void *hip_stream);
+
+/*
+ * The update step of k-means alone (Section 2): centroids[j] = mean of the rows
+ * of x [n][D] with assign[i] == j (fp64 sums in a fixed order, rounded to
+ * fp32); a cluster without rows keeps the value centroids[j] holds on entry.
+ * Used where the assignment is given (approximate or external assignment,
+ * Section 3.1).
+ */
+int ivf_cluster_means(const float *x, int64_t n, int D, const int32_t *assign, int64_t K,
+                      float *centroids, void *hip_stream);
+
+/*
+ * Neighbour table NN_L (Eq. (2)): for every centroid its L nearest among the
+ * other centroids, ordered by (distance, id): nbr [K][L] int32 and
+ * cs_dist2 [K][L] = ||c - s_l||^2.  1 <= L < K, L <= 4095.
+ */
+int ivf_neighbours(const float *centroids, int64_t K, int D, int L, int32_t *nbr, float *cs_dist2,
+                   void *hip_stream);
+
+/*
+ * Scaling factor per region (Section 3.2, Eqs. (8)-(12)): for each of the n
+ * training points x [n][D] with region[n], the neighbour s_l whose line through
+ * c leaves the smallest residual with the coefficient clamped to [0,1]
+ * (Eqs. (10)-(11), lowest l on ties); then alpha_r = sum (x-c)^T(s_l-c) /
+ * sum ||s_l-c||^2 over the region's points (Eq. (12)), clamped to [0,1].  A
+ * region without training points, or whose denominator is 0, gets the ratio
+ * of the two sums taken over all regions.  All sums in fp64.  alpha [K].
+ */
+int ivf_learn_alpha(const float *centroids, int64_t K, int D, const int32_t *nbr, int L,
+                    const float *x, int64_t n, const int32_t *region, float *alpha, void *hip_stream);
+
+/*
+ * PQ codebooks (Section 2): one 256-codeword k-means per block of D/M
+ * dimensions of the displacements E [n][D] (the out_residual of ivf_encode).
+ * Codeword j of every block starts as that block of row init_idx[j] (device,
+ * int64, 256 entries); `iters` Lloyd rounds as in ivf_kmeans (nearest codeword
+ * by (distance, index), means in fp64, empty codewords kept).  codebook
+ * [M][256][D/M].  D/M must be 4, 6, 8, 12 or 16 and n >= 256.
+ */
+int ivf_pq_train(const float *E, int64_t n, int D, int M, int iters, const int64_t *init_idx,
+                 float *codebook, void *hip_stream);
+
+/*
+ * The 256-level scalar quantiser of the per-point term of Eq. (6): table
+ * [256] = 1-D Lloyd on the n values t (the out_const_t of ivf_encode), started
+ * at the (j + 1/2)/256 quantiles, `iters` rounds (nearest level in fp64, lower
+ * index on ties; a level without values keeps its entry), sorted ascending
+ * after every round and rounded to fp32.
+ */
+int ivf_lloyd_1d(const float *t, int64_t n, int iters, float *table, void *hip_stream);
+
+/*
+ * Grouped order (Section 3.2: the points of a region are stored by subregion):
+ * a stable counting sort of n items by bucket[i] in [0, nbuckets), here
+ * bucket = region * L + subregion.  perm [n] lists the item indices bucket by
+ * bucket, ascending inside a bucket (so position order is (region, subregion,
+ * id) order); offsets [nbuckets + 1] uint32 are the bucket boundaries in perm.
+ * Also used with bucket = cluster to list the members of k-means clusters.
+ */
+int ivf_group(const int32_t *bucket, int64_t n, int64_t nbuckets, int32_t *perm, uint32_t *offsets,
+              void *hip_stream);
+
+/* bucket[i] = region[i] * L + sub[i], the subregion id points are grouped by.  Asynchronous. */
+int ivf_bucket_ids(const int32_t *region, const int32_t *sub, int64_t n, int L, int32_t *bucket,
+                   void *hip_stream);
+
+/*
+ * dst row j = src row perm[j] for n rows of row_bytes bytes (codes, constant
+ * bytes or ids into grouped order).  src and dst must not overlap.
  * Asynchronous on hip_stream.
  */
-int ivf_alpha_stats(const float *centroids, int64_t K, int D, const int32_t *nbr, int L,
-                    const float *x, int64_t n, const int32_t *region, double *num, double *den,
+int ivf_gather_rows(const void *src, int64_t row_bytes, const int32_t *perm, int64_t n, void *dst,
                     void *hip_stream);
 
 /*

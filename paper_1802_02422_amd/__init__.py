@@ -20,7 +20,15 @@ from .binding import (  # noqa: F401
     ivf_num_kept,
     ivf_coarse_topk,
     ivf_encode,
-    ivf_alpha_stats,
+    ivf_kmeans,
+    ivf_cluster_means,
+    ivf_bucket_ids,
+    ivf_neighbours,
+    ivf_learn_alpha,
+    ivf_pq_train,
+    ivf_lloyd_1d,
+    ivf_group,
+    ivf_gather_rows,
     ivf_last_error,
     ivf_profile_enable,
     ivf_copy_bytes,

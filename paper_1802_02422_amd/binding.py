@@ -57,7 +57,15 @@ def load_library():
     lib.ivf_num_kept.restype = i64
     lib.ivf_coarse_topk.argtypes = [vp, i64, i32, vp, i64, i32, vp, vp, vp]
     lib.ivf_encode.argtypes = [C.POINTER(_Desc), vp, i64, vp, vp, vp, vp, vp, vp, vp, vp]
-    lib.ivf_alpha_stats.argtypes = [vp, i64, i32, vp, i32, vp, i64, vp, vp, vp, vp]
+    lib.ivf_kmeans.argtypes = [vp, i64, i32, i64, i32, vp, vp, vp, vp]
+    lib.ivf_cluster_means.argtypes = [vp, i64, i32, vp, i64, vp, vp]
+    lib.ivf_bucket_ids.argtypes = [vp, vp, i64, i32, vp, vp]
+    lib.ivf_neighbours.argtypes = [vp, i64, i32, i32, vp, vp, vp]
+    lib.ivf_learn_alpha.argtypes = [vp, i64, i32, vp, i32, vp, i64, vp, vp, vp]
+    lib.ivf_pq_train.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp]
+    lib.ivf_lloyd_1d.argtypes = [vp, i64, i32, vp, vp]
+    lib.ivf_group.argtypes = [vp, i64, i64, vp, vp, vp]
+    lib.ivf_gather_rows.argtypes = [vp, i64, vp, i64, vp, vp]
     lib.ivf_profile_enable.argtypes = [vp, i32]
     lib.ivf_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.ivf_copy_bytes.argtypes = [vp, vp, i64, vp]
@@ -274,9 +282,53 @@ def ivf_encode(trained: IndexDesc, x: torch.Tensor, region_in: Optional[torch.Te
     return region, sub, codes, byte, t
 
 
-def ivf_alpha_stats(centroids: torch.Tensor, nbr: torch.Tensor, x: torch.Tensor, region: torch.Tensor,
-                    num: torch.Tensor, den: torch.Tensor) -> None:
-    """Accumulate the numerator / denominator sums of the alpha estimate into num, den [K] fp64."""
+def ivf_kmeans(x: torch.Tensor, K: int, iters: int, init_idx: torch.Tensor, want_objective: bool = False):
+    """Region codebook [K, D] by Lloyd's k-means from the rows init_idx of x (and the objective per round)."""
+    n, D = x.shape
+    _dev(x, torch.float32, "x", (n, D))
+    _dev(init_idx, torch.int64, "init_idx", (K,))
+    cent = torch.empty((K, D), dtype=torch.float32, device=x.device)
+    obj = torch.zeros(max(iters, 1), dtype=torch.float64, device=x.device) if want_objective else None
+    _check(load_library().ivf_kmeans(_ptr(x), n, D, K, iters, _ptr(init_idx), _ptr(cent), _ptr(obj), _stream()))
+    return (cent, obj[:iters]) if want_objective else cent
+
+
+def ivf_cluster_means(x: torch.Tensor, assign: torch.Tensor, centroids: torch.Tensor):
+    """One k-means update with a given assignment; returns a new [K, D] tensor (empty clusters keep `centroids`)."""
+    n, D = x.shape
+    K = centroids.shape[0]
+    _dev(x, torch.float32, "x", (n, D))
+    _dev(assign, torch.int32, "assign", (n,))
+    _dev(centroids, torch.float32, "centroids", (K, D))
+    out = centroids.clone()
+    _check(load_library().ivf_cluster_means(_ptr(x), n, D, _ptr(assign), K, _ptr(out), _stream()))
+    return out
+
+
+def ivf_bucket_ids(region: torch.Tensor, sub: torch.Tensor, L: int, out: Optional[torch.Tensor] = None):
+    """bucket = region * L + sub (int32), optionally into a slice of a larger tensor."""
+    n = region.shape[0]
+    _dev(region, torch.int32, "region", (n,))
+    _dev(sub, torch.int32, "sub", (n,))
+    if out is None:
+        out = torch.empty(n, dtype=torch.int32, device=region.device)
+    _dev(out, torch.int32, "bucket", (n,))
+    _check(load_library().ivf_bucket_ids(_ptr(region), _ptr(sub), n, L, _ptr(out), _stream()))
+    return out
+
+
+def ivf_neighbours(centroids: torch.Tensor, L: int):
+    """(nbr [K, L] int32, cs_dist2 [K, L] fp32): the L nearest other centroids of each centroid, by (distance, id)."""
+    K, D = centroids.shape
+    _dev(centroids, torch.float32, "centroids")
+    nbr = torch.empty((K, L), dtype=torch.int32, device=centroids.device)
+    cs = torch.empty((K, L), dtype=torch.float32, device=centroids.device)
+    _check(load_library().ivf_neighbours(_ptr(centroids), K, D, L, _ptr(nbr), _ptr(cs), _stream()))
+    return nbr, cs
+
+
+def ivf_learn_alpha(centroids: torch.Tensor, nbr: torch.Tensor, x: torch.Tensor, region: torch.Tensor):
+    """alpha [K] fp32 from the training points x with their regions."""
     K, D = centroids.shape
     L = nbr.shape[1]
     n = x.shape[0]
@@ -284,10 +336,52 @@ def ivf_alpha_stats(centroids: torch.Tensor, nbr: torch.Tensor, x: torch.Tensor,
     _dev(nbr, torch.int32, "nbr", (K, L))
     _dev(x, torch.float32, "x", (n, D))
     _dev(region, torch.int32, "region", (n,))
-    _dev(num, torch.float64, "num", (K,))
-    _dev(den, torch.float64, "den", (K,))
-    _check(load_library().ivf_alpha_stats(_ptr(centroids), K, D, _ptr(nbr), L, _ptr(x), n, _ptr(region),
-                                          _ptr(num), _ptr(den), _stream()))
+    alpha = torch.empty(K, dtype=torch.float32, device=x.device)
+    _check(load_library().ivf_learn_alpha(_ptr(centroids), K, D, _ptr(nbr), L, _ptr(x), n, _ptr(region),
+                                          _ptr(alpha), _stream()))
+    return alpha
+
+
+def ivf_pq_train(E: torch.Tensor, M: int, iters: int, init_idx: torch.Tensor):
+    """PQ codebooks [M, 256, D/M] trained on the displacements E [n, D]."""
+    n, D = E.shape
+    _dev(E, torch.float32, "E", (n, D))
+    _dev(init_idx, torch.int64, "init_idx", (256,))
+    cb = torch.empty((M, 256, D // M), dtype=torch.float32, device=E.device)
+    _check(load_library().ivf_pq_train(_ptr(E), n, D, M, iters, _ptr(init_idx), _ptr(cb), _stream()))
+    return cb
+
+
+def ivf_lloyd_1d(t: torch.Tensor, iters: int):
+    """256-level scalar quantiser table (ascending fp32) for the values t."""
+    n = t.shape[0]
+    _dev(t, torch.float32, "t", (n,))
+    table = torch.empty(256, dtype=torch.float32, device=t.device)
+    _check(load_library().ivf_lloyd_1d(_ptr(t), n, iters, _ptr(table), _stream()))
+    return table
+
+
+def ivf_group(bucket: torch.Tensor, nbuckets: int):
+    """(perm [n] int32, offsets [nbuckets + 1] uint32 bit patterns as int32): items listed bucket by bucket, stable."""
+    n = bucket.shape[0]
+    _dev(bucket, torch.int32, "bucket", (n,))
+    perm = torch.empty(n, dtype=torch.int32, device=bucket.device)
+    off = torch.empty(nbuckets + 1, dtype=torch.int32, device=bucket.device)
+    _check(load_library().ivf_group(_ptr(bucket), n, nbuckets, _ptr(perm), _ptr(off), _stream()))
+    return perm, off
+
+
+def ivf_gather_rows(src: torch.Tensor, perm: torch.Tensor, out: Optional[torch.Tensor] = None):
+    """out[j] = src[perm[j]] along dim 0 (rows copied byte for byte)."""
+    n = perm.shape[0]
+    if not (src.is_cuda and src.is_contiguous()):
+        raise IvfError("src must be a contiguous device tensor")
+    _dev(perm, torch.int32, "perm", (n,))
+    row_bytes = src.element_size() * (src.numel() // max(src.shape[0], 1))
+    if out is None:
+        out = torch.empty((n,) + tuple(src.shape[1:]), dtype=src.dtype, device=src.device)
+    _check(load_library().ivf_gather_rows(_ptr(src), row_bytes, _ptr(perm), n, _ptr(out), _stream()))
+    return out
 
 
 STAGE_NAMES = ("coarse_gemm", "probe_select", "score_prune", "lut", "scan", "merge")

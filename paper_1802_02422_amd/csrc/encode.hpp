@@ -160,7 +160,7 @@ __global__ __launch_bounds__(64) void encode_kernel(
 // is one broadcast LDS read, the running minimum stays in the lane (no cross-lane reduction), and
 // the arithmetic per (point, codeword) is the same sequence of fused multiply-adds as in
 // encode_kernel: the codes are identical.  Also the per-point constant t = 2<mu, r> + ||r||^2
-// of Eq. (6) and its nearest table entry, lowest index on ties.  E and MU are [n][D] fp32.
+// of Eq. (6) and its nearest table entry, lowest index on ties.  E and MU are [n][D] fp32 (MU == NULL: codes only, the assignment step of the codebook training).
 // A workgroup encodes several batches of blockDim.x points (grid-stride).
 template <int DS>
 __global__ __launch_bounds__(1024) void pq_encode_kernel(
@@ -195,10 +195,12 @@ __global__ __launch_bounds__(1024) void pq_encode_kernel(
             }
             out_codes[i * M + m] = (uint8_t)bj;
             const float *cw = cwm + bj * DS;
+            if (MU) {
 #pragma unroll
-            for (int t = 0; t < DS; ++t) {
-                const float rv = cw[t];
-                tval = fmaf(2.f * MU[i * D + m * DS + t], rv, fmaf(rv, rv, tval));
+                for (int t = 0; t < DS; ++t) {
+                    const float rv = cw[t];
+                    tval = fmaf(2.f * MU[i * D + m * DS + t], rv, fmaf(rv, rv, tval));
+                }
             }
         }
         if (out_t) out_t[i] = tval;
@@ -211,48 +213,6 @@ __global__ __launch_bounds__(1024) void pq_encode_kernel(
             }
             out_byte[i] = (uint8_t)bj;
         }
-    }
-}
-
-// Step 1 of alpha learning per training point (Eqs. (10)-(11)) and the two sums
-// of Eq. (12), accumulated per region in fp64.
-__global__ __launch_bounds__(64) void alpha_stats_kernel(
-    const float *__restrict__ X, int64_t n, int D, int L, const int32_t *__restrict__ region,
-    const float *__restrict__ C, const int32_t *__restrict__ nbr, double *__restrict__ num,
-    double *__restrict__ den)
-{
-    extern __shared__ float sm[];
-    float *xc = sm;   // x - c
-    const int lane = threadIdx.x;
-    const int64_t i = blockIdx.x;
-    if (i >= n) return;
-    const int64_t r = region[i];
-    for (int t = lane; t < D; t += WAVE) xc[t] = X[i * D + t] - C[r * D + t];
-    wave_sync();
-    double xc2 = 0.0;
-    for (int t = 0; t < D; ++t) xc2 += (double)xc[t] * (double)xc[t];
-    double best = INFINITY, bdot = 0.0, bn2 = 0.0;
-    int bl = 0x7fffffff;
-    for (int l = lane; l < L; l += WAVE) {
-        const float *s = C + (int64_t)nbr[r * L + l] * D;
-        const float *c = C + r * D;
-        double dot = 0.0, n2 = 0.0;
-        for (int t = 0; t < D; ++t) {
-            double u = (double)s[t] - (double)c[t];
-            dot += (double)xc[t] * u;
-            n2 += u * u;
-        }
-        double a = n2 > 0.0 ? dot / n2 : 0.0;
-        a = a < 0.0 ? 0.0 : (a > 1.0 ? 1.0 : a);
-        double res = xc2 - 2.0 * a * dot + a * a * n2;
-        if (res < best) { best = res; bl = l; bdot = dot; bn2 = n2; }
-    }
-    double wbest = best;
-    int wl = bl;
-    wave_argmin(wbest, wl);
-    if (bl == wl && wl != 0x7fffffff) {   // the single lane holding the winner
-        atomicAdd(&num[r], bdot);
-        atomicAdd(&den[r], bn2);
     }
 }
 

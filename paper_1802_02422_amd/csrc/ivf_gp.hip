@@ -20,6 +20,7 @@
 #include "layout.hpp"
 #include "query.hpp"
 #include "scan.hpp"
+#include "train.hpp"
 
 using namespace ivf;
 
@@ -55,6 +56,15 @@ int fail(int code, const char *fmt, ...)
 struct Buf {
     void *p = nullptr;
     size_t bytes = 0;
+};
+
+// device memory released when the scope ends, error returns included (the owner synchronizes first)
+struct DevTmp {
+    void *p = nullptr;
+    DevTmp() = default;
+    DevTmp(const DevTmp &) = delete;
+    DevTmp &operator=(const DevTmp &) = delete;
+    ~DevTmp() { if (p) (void)hipFree(p); }
 };
 
 int ensure(Buf &b, size_t bytes)
@@ -293,15 +303,6 @@ extern "C" int ivf_set_scratch_limit(ivf_index *ix, int64_t bytes)
 }
 
 namespace {
-
-// device memory released when the scope ends, error returns included (the owner synchronizes first)
-struct DevTmp {
-    void *p = nullptr;
-    DevTmp() = default;
-    DevTmp(const DevTmp &) = delete;
-    DevTmp &operator=(const DevTmp &) = delete;
-    ~DevTmp() { if (p) (void)hipFree(p); }
-};
 
 template <class T>
 int dev_copy(T *&dst, const T *src, size_t count, hipStream_t st)
@@ -685,82 +686,130 @@ extern "C" int ivf_search(ivf_index *ix, const float *queries, int64_t nq, int n
                              nullptr, nullptr, nullptr, hip_stream);
 }
 
-extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const float *x, int64_t nq, int P,
-                               int32_t *out_id, float *out_d, void *hip_stream)
+namespace {
+
+// Nearest-centroid assignment (P = 1) with buffers that live across calls: the packed centroid
+// table and the per-chunk query scratch.  No distance tile: the minimum is fused into the GEMM.
+struct ArgminCtx {
+    int64_t K = 0, chunk = 0;
+    int D = 0, Dp = 0;
+    float *cn = nullptr, *csi = nullptr, *xn = nullptr, *xsi = nullptr;
+    _Float16 *cpk = nullptr, *xpk = nullptr;
+    unsigned long long *best = nullptr;
+    ArgminCtx() = default;
+    ArgminCtx(const ArgminCtx &) = delete;
+    ArgminCtx &operator=(const ArgminCtx &) = delete;
+    ~ArgminCtx()
+    {
+        void *owned[] = {cn, csi, xn, xsi, cpk, xpk, best};
+        for (void *p : owned)
+            if (p) (void)hipFree(p);
+    }
+    int init(int64_t K_, int D_, int64_t max_rows)
+    {
+        K = K_; D = D_; Dp = packed_dim(D);
+        chunk = max_rows < (1ll << 20) ? (max_rows > 0 ? max_rows : 1) : (1ll << 20);
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&cn), (size_t)K * sizeof(float)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&cpk), (size_t)packed_rows(K) * Dp * 2 * sizeof(_Float16)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&csi), 2 * sizeof(float)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), (size_t)chunk * sizeof(float)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xsi), (size_t)chunk * sizeof(float)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xpk), (size_t)packed_rows(chunk) * Dp * 2 * sizeof(_Float16)));
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&best), (size_t)chunk * sizeof(unsigned long long)));
+        return IVF_OK;
+    }
+    int set_centroids(const float *centroids, hipStream_t st)
+    {
+        return pack_rows(centroids, K, D, reinterpret_cast<uint32_t *>(csi + 1), cpk, cn, csi, st);
+    }
+    // out_id[i] = nearest centroid of x[i] by (distance, id), out_d[i] (may be NULL) its squared distance
+    int run(const float *x, int64_t n, int32_t *out_id, float *out_d, hipStream_t st)
+    {
+        int rc;
+        for (int64_t q0 = 0; q0 < n; q0 += chunk) {
+            const int64_t m = (n - q0 < chunk) ? n - q0 : chunk;
+            fill_u64_kernel<<<dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st>>>(best, m, ~0ull);
+            LAUNCHCHK("fill_u64_kernel");
+            if ((rc = pack_rows(x + q0 * D, m, D, nullptr, xpk, xn, xsi, st))) return rc;
+            const int tiles_q = (int)((m + GT - 1) / GT);
+            const int64_t grid = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * ((K + GT - 1) / GT);
+            if (grid >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
+            coarse_argmin_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xpk, xn, xsi, m, cpk, cn, csi, K, Dp, best, tiles_q);
+            LAUNCHCHK("coarse_argmin_kernel");
+            argmin_unpack_kernel<<<dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st>>>(best, m, out_id + q0, out_d ? out_d + q0 : nullptr);
+            LAUNCHCHK("argmin_unpack_kernel");
+        }
+        return IVF_OK;
+    }
+};
+
+int check_coarse_args(const float *centroids, int64_t K, int D, const float *x, int64_t nq)
 {
-    if (!centroids || !x || !out_id || !out_d) return fail(IVF_EINVAL, "NULL argument");
-    if (D < 4 || D % 4 || D > IVF_MAX_D) return fail(IVF_EINVAL, "D=%d must be a multiple of 4", D);
-    if (K < 1 || P < 1 || P > K || P > 4096) return fail(IVF_EINVAL, "need 1 <= P <= min(K, 4096)");
-    if (nq < 0 || nq >= (1ll << 31)) return fail(IVF_EINVAL, "nq out of range");
+    if (!centroids || !x) return fail(IVF_EINVAL, "NULL argument");
+    if (D < 4 || D % 4 || D > IVF_MAX_D) return fail(IVF_EINVAL, "D=%d must be a multiple of 4 in [4, %d]", D, IVF_MAX_D);
+    if (K < 1 || K >= (1ll << 31)) return fail(IVF_EINVAL, "K=%lld out of range", (long long)K);
+    if (nq < 0 || nq >= (1ll << 31)) return fail(IVF_EINVAL, "row count out of range");
     if (!aligned16(centroids) || !aligned16(x)) return fail(IVF_EINVAL, "centroids and x must be 16-byte aligned");
-    if (nq == 0) return IVF_OK;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    return IVF_OK;
+}
+
+// The P nearest centroids of every row of x through the distance tile (P > 1), on scratch of its own.
+int coarse_topk_tiled(const float *centroids, int64_t K, int D, const float *x, int64_t nq, int P,
+                      int32_t *out_id, float *out_d, hipStream_t st)
+{
     int64_t tile = (4ll << 30) / (K * (int64_t)sizeof(float));
     if (tile < 1) tile = 1;
     if (tile >= nq) tile = nq;
     else if (tile >= 256) tile -= tile % 256;   // whole blocks of the padded row count
     else if (tile >= GT) tile -= tile % GT;
-    float *cn = nullptr, *xn = nullptr, *Dt = nullptr, *bm = nullptr, *csi = nullptr, *xsi = nullptr;
-    _Float16 *cpk = nullptr, *xpk = nullptr;
     const int64_t nb = (K + BMW - 1) / BMW;
     const int Dp = packed_dim(D);
-    int rc = IVF_OK;
-    auto body = [&]() -> int {
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&cn), (size_t)K * sizeof(float)));
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&cpk), (size_t)packed_rows(K) * Dp * 2 * sizeof(_Float16)));
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&csi), 2 * sizeof(float)));
-        int r2;
-        if ((r2 = pack_rows(centroids, K, D, reinterpret_cast<uint32_t *>(csi + 1), cpk, cn, csi, st))) return r2;
-        if (P == 1) {   // fused per-row minimum, no distance tile
-            const int64_t chunk = 1 << 20;
-            const int64_t cn_rows = nq < chunk ? nq : chunk;
-            unsigned long long *best = nullptr;
-            HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), (size_t)cn_rows * sizeof(float)));
-            HIPCHK(hipMalloc(reinterpret_cast<void **>(&xsi), (size_t)cn_rows * sizeof(float)));
-            HIPCHK(hipMalloc(reinterpret_cast<void **>(&xpk), (size_t)packed_rows(cn_rows) * Dp * 2 * sizeof(_Float16)));
-            HIPCHK(hipMalloc(reinterpret_cast<void **>(&Dt), (size_t)cn_rows * sizeof(unsigned long long)));
-            best = reinterpret_cast<unsigned long long *>(Dt);
-            for (int64_t q0 = 0; q0 < nq; q0 += chunk) {
-                const int64_t n = (nq - q0 < chunk) ? nq - q0 : chunk;
-                HIPCHK(hipMemsetAsync(best, 0xFF, (size_t)n * sizeof(unsigned long long), st));
-                if ((r2 = pack_rows(x + q0 * D, n, D, nullptr, xpk, xn, xsi, st))) return r2;
-                int tiles_q = (int)((n + GT - 1) / GT);
-                int64_t grid = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * ((K + GT - 1) / GT);
-                if (grid >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
-                coarse_argmin_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xpk, xn, xsi, n, cpk, cn, csi, K, Dp, best, tiles_q);
-                LAUNCHCHK("coarse_argmin_kernel");
-                argmin_unpack_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(best, n, out_id + q0, out_d + q0);
-                LAUNCHCHK("argmin_unpack_kernel");
-            }
-            HIPCHK(hipStreamSynchronize(st));
-            return IVF_OK;
-        }
-        const size_t tile_pad = (size_t)packed_rows(tile);   // the GEMM may write whole tiles of rows
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xn), tile_pad * sizeof(float)));
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xsi), tile_pad * sizeof(float)));
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&xpk), (size_t)packed_rows(tile) * Dp * 2 * sizeof(_Float16)));
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&Dt), tile_pad * dt_stride(K) * sizeof(float)));
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&bm), tile_pad * nb * sizeof(float)));
-        for (int64_t q0 = 0; q0 < nq; q0 += tile) {
-            const int64_t n = (nq - q0 < tile) ? nq - q0 : tile;
-            if ((r2 = pack_rows(x + q0 * D, n, D, nullptr, xpk, xn, xsi, st))) return r2;
-            if ((r2 = launch_coarse(xpk, xn, xsi, n, cpk, cn, csi, K, Dp, Dt, bm, st))) return r2;
-            if ((r2 = launch_probe_select(Dt, bm, n, K, P, out_id + q0 * P, out_d + q0 * P, st))) return r2;
-        }
-        HIPCHK(hipStreamSynchronize(st));
-        return IVF_OK;
-    };
-    rc = body();
+    DevTmp cn, csi, cpk, xn, xsi, xpk, Dt, bm;
+    HIPCHK(hipMalloc(&cn.p, (size_t)K * sizeof(float)));
+    HIPCHK(hipMalloc(&cpk.p, (size_t)packed_rows(K) * Dp * 2 * sizeof(_Float16)));
+    HIPCHK(hipMalloc(&csi.p, 2 * sizeof(float)));
+    const size_t tile_pad = (size_t)packed_rows(tile);   // the GEMM may write whole tiles of rows
+    HIPCHK(hipMalloc(&xn.p, tile_pad * sizeof(float)));
+    HIPCHK(hipMalloc(&xsi.p, tile_pad * sizeof(float)));
+    HIPCHK(hipMalloc(&xpk.p, tile_pad * Dp * 2 * sizeof(_Float16)));
+    HIPCHK(hipMalloc(&Dt.p, tile_pad * dt_stride(K) * sizeof(float)));
+    HIPCHK(hipMalloc(&bm.p, tile_pad * nb * sizeof(float)));
+    float *csi_f = static_cast<float *>(csi.p);
+    int rc = pack_rows(centroids, K, D, reinterpret_cast<uint32_t *>(csi_f + 1), static_cast<_Float16 *>(cpk.p),
+                       static_cast<float *>(cn.p), csi_f, st);
+    for (int64_t q0 = 0; q0 < nq && !rc; q0 += tile) {
+        const int64_t n = (nq - q0 < tile) ? nq - q0 : tile;
+        if ((rc = pack_rows(x + q0 * D, n, D, nullptr, static_cast<_Float16 *>(xpk.p), static_cast<float *>(xn.p),
+                            static_cast<float *>(xsi.p), st))) break;
+        if ((rc = launch_coarse(static_cast<_Float16 *>(xpk.p), static_cast<float *>(xn.p), static_cast<float *>(xsi.p), n,
+                                static_cast<_Float16 *>(cpk.p), static_cast<float *>(cn.p), csi_f, K, Dp,
+                                static_cast<float *>(Dt.p), static_cast<float *>(bm.p), st))) break;
+        rc = launch_probe_select(static_cast<float *>(Dt.p), static_cast<float *>(bm.p), n, K, P, out_id + q0 * P,
+                                 out_d + q0 * P, st);
+    }
+    std::string keep = g_err;
+    (void)hipStreamSynchronize(st);   // the temporaries are released on return
+    g_err = keep;
+    return rc;
+}
+
+}  // namespace
+
+extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const float *x, int64_t nq, int P,
+                               int32_t *out_id, float *out_d, void *hip_stream)
+{
+    int rc = check_coarse_args(centroids, K, D, x, nq);
+    if (rc) return rc;
+    if (!out_id || !out_d) return fail(IVF_EINVAL, "NULL argument");
+    if (P < 1 || P > K || P > 4096) return fail(IVF_EINVAL, "need 1 <= P <= min(K, 4096)");
+    if (nq == 0) return IVF_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (P > 1) return coarse_topk_tiled(centroids, K, D, x, nq, P, out_id, out_d, st);
+    ArgminCtx ctx;   // fused per-row minimum, no distance tile
+    if ((rc = ctx.init(K, D, nq))) return rc;
+    if (!(rc = ctx.set_centroids(centroids, st))) rc = ctx.run(x, nq, out_id, out_d, st);
     std::string keep = g_err;
     (void)hipStreamSynchronize(st);
-    if (cn) (void)hipFree(cn);
-    if (xn) (void)hipFree(xn);
-    if (csi) (void)hipFree(csi);
-    if (xsi) (void)hipFree(xsi);
-    if (cpk) (void)hipFree(cpk);
-    if (xpk) (void)hipFree(xpk);
-    if (Dt) (void)hipFree(Dt);
-    if (bm) (void)hipFree(bm);
     g_err = keep;
     return rc;
 }
@@ -852,21 +901,6 @@ extern "C" int ivf_encode(const ivf_index_desc *t, const float *x, int64_t n, co
     return rc;
 }
 
-extern "C" int ivf_alpha_stats(const float *centroids, int64_t K, int D, const int32_t *nbr, int L,
-                               const float *x, int64_t n, const int32_t *region, double *num, double *den,
-                               void *hip_stream)
-{
-    if (!centroids || !nbr || !x || !region || !num || !den) return fail(IVF_EINVAL, "NULL argument");
-    if (D < 1 || D > IVF_MAX_D || K < 1 || L < 1) return fail(IVF_EINVAL, "bad sizes");
-    if (n < 0 || n >= (1ll << 31)) return fail(IVF_EINVAL, "n out of range");
-    if (n == 0) return IVF_OK;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    alpha_stats_kernel<<<dim3((unsigned)n), dim3(64), (size_t)D * sizeof(float), st>>>(
-        x, n, D, L, region, centroids, nbr, num, den);
-    LAUNCHCHK("alpha_stats_kernel");
-    return IVF_OK;
-}
-
 extern "C" int ivf_copy_bytes(void *dst, const void *src, int64_t nbytes, void *hip_stream)
 {
     if (!dst || !src || nbytes < 0 || nbytes % 16 || !aligned16(dst) || !aligned16(src))
@@ -880,3 +914,5 @@ extern "C" int ivf_copy_bytes(void *dst, const void *src, int64_t nbytes, void *
     LAUNCHCHK("copy_bytes_kernel");
     return IVF_OK;
 }
+
+#include "train_api.hpp"

@@ -266,21 +266,3 @@ def test_encode_with_given_regions(tiny):
     r1, s1, c1, b1, _ = ivf.ivf_encode(desc, xd)
     r2, s2, c2, b2, _ = ivf.ivf_encode(desc, xd, region_in=r1)
     assert torch.equal(r1, r2) and torch.equal(s1, s2) and torch.equal(c1, c2) and torch.equal(b1, b2)
-
-
-def test_alpha_stats_match_oracle(tiny):
-    spec, ix, Q, X = tiny
-    n = 20000
-    x = X[:n]
-    reg, _ = orc.assign(x, ix.centroids)
-    dev = torch.device("cuda:0")
-    num = torch.zeros(ix.K, dtype=torch.float64, device=dev)
-    den = torch.zeros(ix.K, dtype=torch.float64, device=dev)
-    ivf.ivf_alpha_stats(torch.from_numpy(ix.centroids).to(dev), torch.from_numpy(ix.nbr).to(dev),
-                        torch.from_numpy(x).to(dev), torch.from_numpy(reg).to(dev), num, den)
-    torch.cuda.synchronize()
-    num, den = num.cpu().numpy(), den.cpu().numpy()
-    ref = orc.learn_alpha(x, reg, ix.centroids, ix.nbr)
-    has = den > 0
-    a = np.clip(num[has] / den[has], 0, 1)
-    np.testing.assert_allclose(a, ref[has], rtol=0, atol=2e-6)

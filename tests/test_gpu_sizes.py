@@ -78,6 +78,42 @@ def test_long_lists_duplicates_and_empty_regions():
     run_and_check(ix, Q[:3], spec, nprobe=1, tau=0.3, k=7, max_near_frac=1.0)
 
 
+def check_stored_points_against_oracle_encoder(spec, mix, mode, desc, ix, n_check=2048):
+    """A sample of the points of the first generated chunk, encoded by the oracle from the raw
+    vectors (region given where the builder was given it), against what the device-built index
+    stores for them: subregion, PQ code and constant byte, near-ties of the oracle's fp64
+    decisions aside."""
+    n0 = min(10_000_000, spec.N)
+    X, lab = sd.draw_points(mix, n0, 0, "base", sorted_labels=(mode == "mixture"))
+    pick = torch.from_numpy(np.random.default_rng(7).choice(n0, n_check, replace=False)).to(X.device)
+    x = X[pick].cpu().numpy()
+    region = lab[pick].int().cpu().numpy() if mode == "mixture" else None
+    del X, lab
+    inv = torch.empty(spec.N, dtype=torch.int32, device=desc.ids.device)
+    inv[desc.ids.long()] = torch.arange(spec.N, dtype=torch.int32, device=desc.ids.device)
+    pos = inv[pick].long().cpu().numpy()
+    del inv
+    enc = orc.encode(x, ix.centroids, ix.nbr, ix.alpha, ix.pq_codebook, ix.const_table, region=region)
+    off = ix.sub_offsets.astype(np.int64)
+    b = enc.region.astype(np.int64) * spec.L + enc.sub
+    inside = (off[b] <= pos) & (pos < off[b + 1])
+    codes_same = inside & (ix.codes[pos] == enc.codes).all(1)
+    byte_same = codes_same & (ix.const_byte[pos] == enc.const_byte)
+    print(f"  stored vs oracle encoder on {n_check} points: subregion {inside.mean():.4f}, "
+          f"code {codes_same.mean():.4f}, byte {byte_same.mean():.4f}", flush=True)
+    assert inside.mean() >= 0.995 and codes_same.mean() >= 0.99 and byte_same.mean() >= 0.98
+    # every point the oracle places elsewhere is a near-tie of its own fp64 choice
+    c64 = ix.centroids.astype(np.float64)
+    stored_bucket = np.searchsorted(off, pos, side="right") - 1
+    for i in np.flatnonzero(~inside):
+        r_st, l_st = divmod(int(stored_bucket[i]), spec.L)
+        def sub_dist(r, l):
+            mu = c64[r] + float(ix.alpha[r]) * (c64[ix.nbr[r, l]] - c64[r])
+            return float(((x[i].astype(np.float64) - mu) ** 2).sum())
+        d_st, d_or = sub_dist(r_st, l_st), sub_dist(int(enc.region[i]), int(enc.sub[i]))
+        assert abs(d_st - d_or) <= 1e-5 * max(d_or, 1.0), (i, d_st, d_or)
+
+
 def full_size_case(name, n_sample, extra_batches=()):
     spec = sd.WORKLOADS[name]
     dev = torch.device("cuda:0")
@@ -87,6 +123,7 @@ def full_size_case(name, n_sample, extra_batches=()):
     print("built", name, stats, flush=True)
     Q = sd.draw_queries(mix, spec.nq).contiguous()
     ix = download_index(desc, spec)
+    check_stored_points_against_oracle_encoder(spec, mix, mode, desc, ix)
     handle = ivf.ivf_load_index(desc)
     desc.codes = desc.const_byte = desc.ids = None
     torch.cuda.empty_cache()
@@ -117,12 +154,12 @@ def full_size_case(name, n_sample, extra_batches=()):
 
 def test_full_size_deep10m_sampled_queries():
     print("case: deep10m full size", flush=True)
-    full_size_case("deep10m", 64)
+    full_size_case("deep10m", 128)
 
 
 def test_full_size_sift10m_sampled_queries():
     print("case: sift10m full size", flush=True)
-    full_size_case("sift10m", 64)
+    full_size_case("sift10m", 128)
 
 
 def test_full_size_deep100m_latency_batches():
@@ -132,7 +169,7 @@ def test_full_size_deep100m_latency_batches():
 
 def test_full_size_deep1b_sampled_queries():
     print("case: deep1b full size", flush=True)
-    full_size_case("deep1b", 32)
+    full_size_case("deep1b", 256)
 
 
 @pytest.mark.parametrize("mode", ["zero", "one", "mixed"])
