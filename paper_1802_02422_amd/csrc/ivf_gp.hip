@@ -144,7 +144,7 @@ int launch_coarse(const _Float16 *xp, const float *xn, const float *xsi, int64_t
     int tiles_q = (int)((nq + GT - 1) / GT);
     int64_t tiles_c = (K + GT - 1) / GT;
     int64_t grid = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * tiles_c;
-    if (grid >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
+    if (grid >= (1ll << 24)) return fail(IVF_EINVAL, "coarse tile grid too large (more than 2^32 threads)");
     const int stages = Dp / DK;
     if ((stages == 6 || stages == 8) && K % GT == 0) {
         // Query tile held in registers, centroid tiles swept.  The kernel works on whole tiles: the
@@ -154,7 +154,7 @@ int launch_coarse(const _Float16 *xp, const float *xn, const float *xsi, int64_t
         static_assert(per_wg % SWEEP_BMC == 0, "a workgroup's first tile starts a 64-byte piece of the block minima");
         const int64_t groups = (tiles_c + per_wg - 1) / per_wg;
         const int64_t g2 = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * groups;
-        if (g2 >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
+        if (g2 >= (1ll << 24)) return fail(IVF_EINVAL, "coarse tile grid too large (more than 2^32 threads)");
         if (stages == 6)
             coarse_gemm_sweep_kernel<6><<<dim3((unsigned)g2), dim3(256), 0, st>>>(xp, xn, xsi, (int64_t)tiles_q * GT, Cp, cn, csi, K, Dt, ldt, bm, nb, tiles_q, (int)tiles_c, per_wg);
         else
@@ -708,7 +708,13 @@ struct ArgminCtx {
     int init(int64_t K_, int D_, int64_t max_rows)
     {
         K = K_; D = D_; Dp = packed_dim(D);
-        chunk = max_rows < (1ll << 20) ? (max_rows > 0 ? max_rows : 1) : (1ll << 20);
+        // rows per launch: at most 2^20, and few enough that the grid (one workgroup of 256 threads per
+        // tile of 128 rows x 128 centroids) stays below the 2^32 threads a launch may have
+        const int64_t tiles_c = (K + GT - 1) / GT;
+        int64_t max_tq = ((1ll << 24) - 1) / tiles_c / N_XCD * N_XCD;
+        if (max_tq < N_XCD) return fail(IVF_EINVAL, "K=%lld: too many centroid tiles for one launch", (long long)K);
+        chunk = max_tq * GT < (1ll << 20) ? max_tq * GT : (1ll << 20);
+        if (max_rows < chunk) chunk = max_rows > 0 ? max_rows : 1;
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&cn), (size_t)K * sizeof(float)));
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&cpk), (size_t)packed_rows(K) * Dp * 2 * sizeof(_Float16)));
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&csi), 2 * sizeof(float)));
@@ -733,7 +739,7 @@ struct ArgminCtx {
             if ((rc = pack_rows(x + q0 * D, m, D, nullptr, xpk, xn, xsi, st))) return rc;
             const int tiles_q = (int)((m + GT - 1) / GT);
             const int64_t grid = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * ((K + GT - 1) / GT);
-            if (grid >= (1ll << 31)) return fail(IVF_EINVAL, "coarse tile grid too large");
+            if (grid >= (1ll << 24)) return fail(IVF_EINVAL, "coarse tile grid too large");
             coarse_argmin_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xpk, xn, xsi, m, cpk, cn, csi, K, Dp, best, tiles_q);
             LAUNCHCHK("coarse_argmin_kernel");
             argmin_unpack_kernel<<<dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st>>>(best, m, out_id + q0, out_d ? out_d + q0 : nullptr);

@@ -110,7 +110,7 @@ extern "C" int ivf_gather_rows(const void *src, int64_t row_bytes, const int32_t
     const uintptr_t al = reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst) | (uintptr_t)row_bytes;
     const int vec = (al % 16 == 0) ? 16 : (al % 8 == 0) ? 8 : (al % 4 == 0) ? 4 : 1;
     const int64_t threads = n * (row_bytes / vec);
-    if (threads / 256 >= (1ll << 31)) return fail(IVF_EINVAL, "too many rows for one launch");
+    if (threads >= (1ll << 32) - 256) return fail(IVF_EINVAL, "too many rows for one launch");
     gather_rows_kernel<<<dim3(grid_for(threads)), dim3(256), 0, static_cast<hipStream_t>(hip_stream)>>>(
         static_cast<const uint8_t *>(src), row_bytes, perm, n, static_cast<uint8_t *>(dst), vec);
     LAUNCHCHK("gather_rows_kernel");
