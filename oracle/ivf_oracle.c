@@ -165,21 +165,51 @@ void orc_prune(const double *scores, int64_t nq, int64_t P, int L, const int32_t
 
 /* ------------------------------------------- stage 4: lookup tables -------- */
 
+/* Global rotation in front of the product quantiser (Section 4: the
+ * displacements are OPQ-compressed, one rotation shared by all regions):
+ * out[i] = R x[i] for a D x D matrix R, row-major, out[i][a] = sum_b R[a][b] x[i][b].
+ * With an orthogonal R and y = R e quantised to r, the point is mu + R^T r and
+ *   ||q - mu - R^T r||^2 = ||q - mu||^2 - 2<R q, r> + (2<R mu, r> + ||r||^2):
+ * the lookup table is built from the rotated query and the per-point constant
+ * from the rotated subcentroid. */
+void orc_rotate(const double *X, int64_t n, int D, const float *R, double *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i)
+        for (int a = 0; a < D; ++a) {
+            double s = 0.0;
+            for (int b = 0; b < D; ++b) s += (double)R[(int64_t)a * D + b] * X[i * D + b];
+            out[i * D + a] = s;
+        }
+}
+
 /* Per-query table of the inner-product term of Eq. (6):
  * T[q][m][j] = -2 <q_m, r^m_j>, with q_m the m-th block of D/M consecutive
- * dimensions and codebook laid out [M][256][D/M]. */
-void orc_lut(const float *Q, int64_t nq, int D, int M, const float *codebook, double *T)
+ * dimensions and codebook laid out [M][256][D/M].  With a rotation (may be
+ * NULL) q is replaced by R q. */
+void orc_lut(const float *Q, int64_t nq, int D, int M, const float *codebook, const float *rotation,
+             double *T)
 {
     int ds = D / M;
 #pragma omp parallel for schedule(static)
-    for (int64_t q = 0; q < nq; ++q)
+    for (int64_t q = 0; q < nq; ++q) {
+        double *qr = (double *)malloc((size_t)D * sizeof(double));
+        for (int a = 0; a < D; ++a) qr[a] = (double)Q[q * D + a];
+        if (rotation) {
+            double *qin = (double *)malloc((size_t)D * sizeof(double));
+            memcpy(qin, qr, (size_t)D * sizeof(double));
+            orc_rotate(qin, 1, D, rotation, qr);
+            free(qin);
+        }
         for (int m = 0; m < M; ++m)
             for (int j = 0; j < 256; ++j) {
                 double s = 0.0;
                 for (int i = 0; i < ds; ++i)
-                    s += (double)Q[q * D + m * ds + i] * (double)codebook[((int64_t)m * 256 + j) * ds + i];
+                    s += qr[m * ds + i] * (double)codebook[((int64_t)m * 256 + j) * ds + i];
                 T[(q * M + m) * 256 + j] = -2.0 * s;
             }
+        free(qr);
+    }
 }
 
 /* --------------------------------------------- stage 5: ADC scan ----------- */
@@ -293,6 +323,7 @@ typedef struct {
     const uint8_t *codes;      /* N*M */
     const uint8_t *const_byte; /* N */
     const int32_t *ids;        /* N */
+    const float *rotation;     /* D*D or NULL: rotation in front of the PQ (Section 4, OPQ) */
 } orc_index;
 
 /* Stages 1-6 in order for every query.  n_scanned (may be NULL) receives the
@@ -315,7 +346,7 @@ void orc_search(const orc_index *ix, const float *Q, int64_t nq, int64_t P, doub
         orc_probe(qv, 1, ix->centroids, ix->K, D, P, probe_id, probe_d);
         orc_scores(qv, 1, ix->centroids, D, ix->nbr, L, ix->alpha, ix->cs_dist2, probe_id, P, scores);
         orc_prune(scores, 1, P, L, probe_id, S, kept_sub, kept_score);
-        orc_lut(qv, 1, D, M, ix->pq_codebook, T);
+        orc_lut(qv, 1, D, M, ix->pq_codebook, ix->rotation, T);
         orc_scan_count(kept_sub, NULL, 1, S, ix->sub_offsets, &count);
         int64_t *cand_pos = (int64_t *)malloc((size_t)(count > 0 ? count : 1) * sizeof(int64_t));
         double *cand_dist = (double *)malloc((size_t)(count > 0 ? count : 1) * sizeof(double));

@@ -14,6 +14,7 @@ import ctypes as C
 import os
 import subprocess
 from dataclasses import dataclass
+from typing import Optional
 
 import numpy as np
 
@@ -128,11 +129,21 @@ def prune(sc, probe_id, prune_frac):
     return kept, ks
 
 
+def rotate(X, R):
+    """Rows of X (fp64) multiplied by the D x D matrix R: out[i] = R x[i]."""
+    X, R = _f64(X), _f32(R)
+    n, D = X.shape
+    out = np.empty((n, D), np.float64)
+    lib().orc_rotate(_p(X), I64(n), INT(D), _p(R), _p(out))
+    return out
+
+
 def lut(Q, ix):
     Q = _f32(Q)
     nq, D = Q.shape
     T = np.empty((nq, ix.M, 256), np.float64)
-    lib().orc_lut(_p(Q), I64(nq), INT(D), INT(ix.M), _p(ix.pq_codebook), _p(T))
+    rot = None if ix.rotation is None else _f32(ix.rotation)
+    lib().orc_lut(_p(Q), I64(nq), INT(D), INT(ix.M), _p(ix.pq_codebook), _p(rot), _p(T))
     return T
 
 
@@ -177,16 +188,17 @@ class _CIndex(C.Structure):
                 ("centroids", C.c_void_p), ("nbr", C.c_void_p), ("alpha", C.c_void_p),
                 ("cs_dist2", C.c_void_p), ("pq_codebook", C.c_void_p), ("const_table", C.c_void_p),
                 ("sub_offsets", C.c_void_p), ("codes", C.c_void_p), ("const_byte", C.c_void_p),
-                ("ids", C.c_void_p)]
+                ("ids", C.c_void_p), ("rotation", C.c_void_p)]
 
 
 def search(ix, Q, nprobe, prune_frac, k):
     """Whole query path: (ids [nq,k] int32, dists [nq,k] fp64, codes scanned [nq])."""
     Q = _f32(Q)
     nq = Q.shape[0]
+    rot = None if ix.rotation is None else _f32(ix.rotation)     # kept alive until the call returns
     ci = _CIndex(ix.D, ix.M, ix.L, ix.K, ix.N, *[a.ctypes.data for a in (
         ix.centroids, ix.nbr, ix.alpha, ix.cs_dist2, ix.pq_codebook, ix.const_table, ix.sub_offsets,
-        ix.codes, ix.const_byte, ix.ids)])
+        ix.codes, ix.const_byte, ix.ids)], None if rot is None else rot.ctypes.data)
     oi = np.empty((nq, k), np.int32)
     od = np.empty((nq, k), np.float64)
     ns = np.empty(nq, np.int64)
@@ -372,6 +384,7 @@ class Index:
     codes: np.ndarray        # [N, M] uint8, grouped order
     const_byte: np.ndarray   # [N] uint8, grouped order
     ids: np.ndarray          # [N] int32, original id of each grouped position
+    rotation: Optional[np.ndarray] = None   # [D, D] fp32 or None: rotation in front of the PQ
 
 
 @dataclass
@@ -384,14 +397,19 @@ class Encoded:
     mu: np.ndarray
 
 
-def encode(X, Cn, nbr, alpha, codebook, const_table=None, region=None) -> Encoded:
+def encode(X, Cn, nbr, alpha, codebook, const_table=None, region=None, rotation=None) -> Encoded:
     """Index-time encoding of points: region, subregion (Eq. 3), PQ code of the
-    displacement (Eq. 4), per-point constant t and its byte."""
+    displacement (Eq. 4), per-point constant t and its byte.  With a rotation the
+    PQ sees R (x - mu) and the constant is taken with R mu."""
     if region is None:
         region, _ = assign(X, Cn)
     sub, mu, res = sub_assign(X, region, Cn, nbr, alpha)
-    codes = pq_encode(res, codebook)
-    t = const_term(mu, codes, codebook)
+    if rotation is not None:
+        codes = pq_encode(rotate(res, rotation), codebook)
+        t = const_term(rotate(mu, rotation), codes, codebook)
+    else:
+        codes = pq_encode(res, codebook)
+        t = const_term(mu, codes, codebook)
     byte = quantize_1d(t, const_table) if const_table is not None else None
     return Encoded(region, sub, codes, t, byte, mu)
 
@@ -408,7 +426,7 @@ def group(region, sub, L, K):
 
 
 def build_index(X_train, X_base, K, L, M, init_centroids_idx, init_pq_idx, kmeans_iters=10, pq_iters=20,
-                const_iters=20, ids=None) -> Index:
+                const_iters=20, ids=None, rotation=None) -> Index:
     """Train on the hold-out sample, then encode and group the base set
     (Section 3.2; all trainable parameters come from the learning set, Section 4)."""
     X_train, X_base = _f32(X_train), _f32(X_base)
@@ -418,14 +436,16 @@ def build_index(X_train, X_base, K, L, M, init_centroids_idx, init_pq_idx, kmean
     reg_t, _ = assign(X_train, cent)
     alpha = learn_alpha(X_train, reg_t, cent, nbr)
     _, mu_t, res_t = sub_assign(X_train, reg_t, cent, nbr, alpha)
+    if rotation is not None:
+        mu_t, res_t = rotate(mu_t, rotation), rotate(res_t, rotation)
     cb, _ = pq_train(res_t, M, pq_iters, init_pq_idx)
     codes_t = pq_encode(res_t, cb)
     t_t = const_term(mu_t, codes_t, cb)
     table = lloyd_1d(t_t, const_iters)
-    enc = encode(X_base, cent, nbr, alpha, cb, table)
+    enc = encode(X_base, cent, nbr, alpha, cb, table, rotation=rotation)
     perm, off = group(enc.region, enc.sub, L, K)
     N = X_base.shape[0]
     ids = np.arange(N, dtype=np.int32) if ids is None else _i32(ids)
     return Index(D, M, L, K, N, cent, nbr, alpha, cs, cb, table, off,
                  np.ascontiguousarray(enc.codes[perm]), np.ascontiguousarray(enc.const_byte[perm]),
-                 np.ascontiguousarray(ids[perm]))
+                 np.ascontiguousarray(ids[perm]), None if rotation is None else _f32(rotation))

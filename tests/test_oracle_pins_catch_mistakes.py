@@ -94,6 +94,14 @@ MUTATIONS = {
         "if (collected < R) collected += (int64_t)sub_offsets[b + 1] - (int64_t)sub_offsets[b];",
         "if (collected < R) collected += 1;",
         ["test_budget_walk_against_python_traversal", "test_budget_nested_and_unbounded_budget_is_plain_search"]),
+    "rotation_transposed": (
+        "for (int b = 0; b < D; ++b) s += (double)R[(int64_t)a * D + b] * X[i * D + b];",
+        "for (int b = 0; b < D; ++b) s += (double)R[(int64_t)b * D + a] * X[i * D + b];",
+        ["test_rotate_is_the_matrix_product", "test_rotated_scan_equals_distance_to_points_decoded_in_the_original_space"]),
+    "rotation_not_applied_to_query": (
+        "            orc_rotate(qin, 1, D, rotation, qr);",
+        "            (void)qin;",
+        ["test_rotated_scan_equals_distance_to_points_decoded_in_the_original_space"]),
     "subcentroid_weights": (
         "double mu = (double)c[t] + a * ((double)s[t] - (double)c[t]);",
         "double mu = (double)c[t] + (1.0 - a) * ((double)s[t] - (double)c[t]);",

@@ -340,3 +340,72 @@ def test_budget_nested_and_unbounded_budget_is_plain_search(tiny):
             ref = sorted(zip(cd.tolist(), ix.ids[cp].tolist()))[:10]
             got = [(d, i) for d, i in zip(d_r[q].tolist(), ids_r[q].tolist()) if i >= 0]
             assert got == ref
+
+
+# ------------------------------------------------- rotation in front of the PQ
+
+
+def random_rotation(D, rng):
+    q, r = np.linalg.qr(rng.standard_normal((D, D)))
+    return (q * np.sign(np.diag(r))[None, :]).astype(np.float32)
+
+
+def test_rotate_is_the_matrix_product(rng):
+    X = rng.standard_normal((7, 5))
+    R = rng.standard_normal((5, 5)).astype(np.float32)          # not symmetric: a transposed operand shows
+    np.testing.assert_allclose(orc.rotate(X, R), X @ R.astype(np.float64).T, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(orc.rotate(X, np.eye(5, dtype=np.float32)), X, rtol=0, atol=0)
+
+
+def rotated_tiny(tiny, rng):
+    """The tiny index re-encoded with a random orthogonal rotation in front of its (unchanged) PQ."""
+    spec, ix, Q, X = tiny
+    R = random_rotation(spec.D, rng)
+    enc = orc.encode(X, ix.centroids, ix.nbr, ix.alpha, ix.pq_codebook, ix.const_table, rotation=R)
+    perm, off = orc.group(enc.region, enc.sub, spec.L, spec.K)
+    ixr = orc.Index(spec.D, spec.M, spec.L, spec.K, spec.N, ix.centroids, ix.nbr, ix.alpha, ix.cs_dist2,
+                    ix.pq_codebook, ix.const_table, off, np.ascontiguousarray(enc.codes[perm]),
+                    np.ascontiguousarray(enc.const_byte[perm]), np.arange(spec.N, dtype=np.int32)[perm].copy(), R)
+    return ixr, R
+
+
+def test_rotation_identity_changes_nothing(tiny):
+    spec, ix, Q, X = tiny
+    eye = np.eye(spec.D, dtype=np.float32)
+    a = orc.encode(X[:3000], ix.centroids, ix.nbr, ix.alpha, ix.pq_codebook, ix.const_table)
+    b = orc.encode(X[:3000], ix.centroids, ix.nbr, ix.alpha, ix.pq_codebook, ix.const_table, rotation=eye)
+    assert (a.codes == b.codes).all() and (a.const_byte == b.const_byte).all() and (a.t == b.t).all()
+    import dataclasses
+    ixe = dataclasses.replace(ix, rotation=eye)
+    r0, r1 = orc.search(ix, Q[:20], spec.nprobe, spec.prune_frac, spec.k), orc.search(ixe, Q[:20], spec.nprobe, spec.prune_frac, spec.k)
+    assert (r0[0] == r1[0]).all() and (r0[1] == r1[1]).all()
+
+
+def test_rotated_scan_equals_distance_to_points_decoded_in_the_original_space(tiny, rng):
+    """With an orthogonal R the stored point is mu + R^T decode(code); Eq. (6) with the table of the
+    rotated query and the unquantised constant of the rotated subcentroid must give the plain
+    distance to that point."""
+    spec, _, Q, X = tiny
+    ixr, R = rotated_tiny(tiny, rng)
+    reg, sub = pos_to_bucket(ixr)
+    mu, dec = explicit_points(ixr, reg, sub)                   # dec lives in the rotated space
+    back = dec @ R.astype(np.float64)                          # R^T dec, row-wise
+    mu_rot = mu @ R.astype(np.float64).T
+    t_exact = 2.0 * (mu_rot * dec).sum(1) + (dec * dec).sum(1)
+    # the encoder minimised the error of R (x - mu): decoding lands near the original points
+    xg = X[ixr.ids].astype(np.float64)
+    assert ((xg - mu - back) ** 2).sum(1).mean() < 0.7 * ((xg - mu) ** 2).sum(1).mean()   # (the codebook was trained without the rotation)
+    nq = 10
+    pid, _ = orc.probe(Q[:nq], ixr.centroids, spec.nprobe)
+    kept, ks = orc.prune(orc.scores(Q[:nq], ixr, pid), pid, spec.prune_frac)
+    start, pos, dist = orc.scan(ixr, kept, ks, orc.lut(Q[:nq], ixr), const_exact=t_exact)
+    for q in range(nq):
+        p = pos[start[q]:start[q + 1]]
+        direct = ((Q[q].astype(np.float64)[None] - mu[p] - back[p]) ** 2).sum(1)
+        np.testing.assert_allclose(dist[start[q]:start[q + 1]], direct, rtol=0, atol=2e-6)
+    # the stored constant byte is the nearest table entry to that t
+    np.testing.assert_array_equal(ixr.const_byte, orc.quantize_1d(t_exact, ixr.const_table))
+    # and the one-call search is the staged composition
+    oi, od, _ = orc.search(ixr, Q[:nq], spec.nprobe, spec.prune_frac, spec.k)
+    st = orc.search_staged(ixr, Q[:nq], spec.nprobe, spec.prune_frac, spec.k)
+    assert (oi == st["ids"]).all() and (od == st["dists"]).all()
