@@ -40,7 +40,8 @@ def download_index(desc, spec):
     h = lambda t: t.cpu().numpy()
     return orc.Index(spec.D, spec.M, spec.L, spec.K, spec.N, h(desc.centroids), h(desc.nbr), h(desc.alpha),
                      h(desc.cs_dist2), h(desc.pq_codebook), h(desc.const_table),
-                     h(desc.sub_offsets).view(np.uint32), h(desc.codes), h(desc.const_byte), h(desc.ids))
+                     h(desc.sub_offsets).view(np.uint32), h(desc.codes), h(desc.const_byte), h(desc.ids),
+                     None if desc.rotation is None else h(desc.rotation))
 
 
 def _omp_threads(n):

@@ -68,6 +68,10 @@ typedef struct ivf_index_desc {
     const uint8_t  *codes;       /* [N][M], grouped order */
     const uint8_t  *const_byte;  /* [N],    grouped order */
     const int32_t  *ids;         /* [N] point id of each grouped position, >= 0 */
+    const float    *rotation;    /* [D][D] row-major orthogonal R in front of the PQ, or NULL (Section 4:
+                                    OPQ-compressed displacements, one rotation shared by all regions): the
+                                    codes quantise R (x - mu), the lookup tables are built from R q and the
+                                    per-point term is 2<R mu, r> + ||r||^2 */
 } ivf_index_desc;
 
 /*
@@ -199,7 +203,7 @@ int ivf_coarse_topk(const float *centroids, int64_t K, int D, const float *x, in
  * displacement (Section 2), the per-point term t = 2<mu, r> + ||r||^2 of
  * Eq. (6) and its nearest entry in const_table (lower index on ties).
  * Only the trained fields of `trained` are read (centroids, nbr, alpha,
- * cs_dist2, pq_codebook, const_table).  const_table may be NULL, then
+ * cs_dist2, pq_codebook, const_table, rotation).  const_table may be NULL, then
  * out_const_byte is not written; pq_codebook may be NULL too (index trained up
  * to alpha only), then only region, subregion and displacement are produced.
  * Outputs: out_region [n] int32, out_sub [n] int32, out_codes [n][M],
@@ -209,6 +213,14 @@ int ivf_coarse_topk(const float *centroids, int64_t K, int D, const float *x, in
 int ivf_encode(const ivf_index_desc *trained, const float *x, int64_t n, const int32_t *region_in,
                int32_t *out_region, int32_t *out_sub, uint8_t *out_codes, uint8_t *out_const_byte,
                float *out_const_t, float *out_residual, void *hip_stream);
+
+/*
+ * out [n][D] = rows of x [n][D] multiplied by the D x D matrix `rotation`
+ * (row-major): out[i] = R x[i].  The rotation of Section 4 (OPQ) applied to
+ * training displacements before ivf_pq_train; ivf_search and ivf_encode apply
+ * the index's own rotation themselves.  x and out may be the same array.  Waits for the stream.
+ */
+int ivf_rotate(const float *x, int64_t n, int D, const float *rotation, float *out, void *hip_stream);
 
 /*
  * ---- Index construction on the device (Section 3.2 "The model" and "Learning

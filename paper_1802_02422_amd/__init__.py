@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     ivf_num_kept,
     ivf_coarse_topk,
     ivf_encode,
+    ivf_rotate,
     ivf_kmeans,
     ivf_cluster_means,
     ivf_bucket_ids,

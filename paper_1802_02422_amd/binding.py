@@ -28,7 +28,7 @@ class _Desc(C.Structure):
                 ("centroids", C.c_void_p), ("nbr", C.c_void_p), ("alpha", C.c_void_p),
                 ("cs_dist2", C.c_void_p), ("pq_codebook", C.c_void_p), ("const_table", C.c_void_p),
                 ("sub_offsets", C.c_void_p), ("codes", C.c_void_p), ("const_byte", C.c_void_p),
-                ("ids", C.c_void_p)]
+                ("ids", C.c_void_p), ("rotation", C.c_void_p)]
 
 
 def library_path() -> str:
@@ -57,6 +57,7 @@ def load_library():
     lib.ivf_num_kept.restype = i64
     lib.ivf_coarse_topk.argtypes = [vp, i64, i32, vp, i64, i32, vp, vp, vp]
     lib.ivf_encode.argtypes = [C.POINTER(_Desc), vp, i64, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.ivf_rotate.argtypes = [vp, i64, i32, vp, vp, vp]
     lib.ivf_kmeans.argtypes = [vp, i64, i32, i64, i32, vp, vp, vp, vp]
     lib.ivf_cluster_means.argtypes = [vp, i64, i32, vp, i64, vp, vp]
     lib.ivf_bucket_ids.argtypes = [vp, vp, i64, i32, vp, vp]
@@ -117,6 +118,7 @@ class IndexDesc:
     codes: Optional[torch.Tensor] = None         # [N, M] uint8
     const_byte: Optional[torch.Tensor] = None    # [N] uint8
     ids: Optional[torch.Tensor] = None           # [N] int32
+    rotation: Optional[torch.Tensor] = None      # [D, D] fp32 rotation in front of the PQ
 
     def _c(self) -> _Desc:
         K, D = self.centroids.shape
@@ -139,7 +141,7 @@ class IndexDesc:
             _dev(self.sub_offsets, self.sub_offsets.dtype, "sub_offsets", (K * L + 1,))
         return _Desc(D, M, L, K, N, *[None if t is None else t.data_ptr() for t in (
             self.centroids, self.nbr, self.alpha, self.cs_dist2, self.pq_codebook, self.const_table,
-            self.sub_offsets, self.codes, self.const_byte, self.ids)])
+            self.sub_offsets, self.codes, self.const_byte, self.ids, _dev(self.rotation, torch.float32, "rotation", (D, D)))])
 
 
 class IndexHandle:
@@ -280,6 +282,16 @@ def ivf_encode(trained: IndexDesc, x: torch.Tensor, region_in: Optional[torch.Te
     if want_residual:
         return region, sub, codes, byte, t, res
     return region, sub, codes, byte, t
+
+
+def ivf_rotate(x: torch.Tensor, rotation: torch.Tensor):
+    """Rows of x multiplied by the D x D rotation: out[i] = R x[i]."""
+    n, D = x.shape
+    _dev(x, torch.float32, "x", (n, D))
+    _dev(rotation, torch.float32, "rotation", (D, D))
+    out = torch.empty_like(x)
+    _check(load_library().ivf_rotate(_ptr(x), n, D, _ptr(rotation), _ptr(out), _stream()))
+    return out
 
 
 def ivf_kmeans(x: torch.Tensor, K: int, iters: int, init_idx: torch.Tensor, want_objective: bool = False):

@@ -198,9 +198,10 @@ struct SearchWs {
     SubDesc *desc = nullptr;
     float *lut = nullptr;
     uint64_t *partial = nullptr;
+    float *qrot = nullptr;       // rotated queries (indexes with a rotation in front of the PQ)
 };
 
-enum { WS_DT, WS_BM, WS_QN, WS_QSI, WS_QPK, WS_PID, WS_PD, WS_DESC, WS_LUT, WS_PARTIAL, WS_COUNT };
+enum { WS_DT, WS_BM, WS_QN, WS_QSI, WS_QPK, WS_PID, WS_PD, WS_DESC, WS_LUT, WS_PARTIAL, WS_QROT, WS_COUNT };
 
 struct SearchPlan {
     int64_t tile = 0;            // queries per pass
@@ -217,7 +218,7 @@ int64_t dt_rows(int64_t n, int64_t K, int Dp)
     return sweep ? (n + GT - 1) / GT * GT : n;
 }
 
-SearchPlan plan_search(int64_t K, int D, int M, int P, int S, int k, int64_t tile)
+SearchPlan plan_search(int64_t K, int D, int M, int P, int S, int k, int64_t tile, bool rotated)
 {
     SearchPlan pl;
     pl.tile = tile;
@@ -246,6 +247,7 @@ SearchPlan plan_search(int64_t K, int D, int M, int P, int S, int k, int64_t til
     pl.bytes[WS_DESC] = (size_t)tile * S * sizeof(SubDesc);
     pl.bytes[WS_LUT] = (size_t)tile * M * 256 * sizeof(float);
     pl.bytes[WS_PARTIAL] = (size_t)tile * pl.merge_n * sizeof(uint64_t);
+    pl.bytes[WS_QROT] = rotated ? (size_t)tile * D * sizeof(float) : 0;
     return pl;
 }
 
@@ -258,11 +260,12 @@ struct ivf_index {
     _Float16 *cpk = nullptr;     // centroids packed for the GEMM
     float *csi = nullptr;        // csi[0] inverse scale of the packed centroids; csi[1] reduction word
     float *codebook = nullptr, *const_table = nullptr;
+    float *rot_t = nullptr;      // transposed rotation in front of the PQ, or NULL
     int32_t *nbr = nullptr, *ids = nullptr;
     uint4 *sub_info = nullptr;   // per subregion: block offset, first position, length
     uint8_t *blocks = nullptr;
     int64_t scratch_limit = 8ll << 30;
-    Buf dt, bm, qn, qpk, qsi, probe_id, probe_d, desc, lut, partial;
+    Buf dt, bm, qn, qpk, qsi, probe_id, probe_d, desc, lut, partial, qrot;
     // optional per-stage timing with HIP events on the caller's stream
     bool profile = false;
     std::vector<hipEvent_t> ev[IVF_N_STAGES + 1];   // ev[s][i], ev[s+1][i] bracket stage s of pass i
@@ -287,7 +290,7 @@ extern "C" void ivf_free_index(ivf_index *ix)
     void *owned[] = {ix->centroids, ix->cnorm, ix->alpha, ix->cst, ix->codebook, ix->const_table,
                      ix->nbr, ix->ids, ix->sub_info, ix->blocks, ix->dt.p, ix->bm.p, ix->qn.p,
                      ix->cpk, ix->csi, ix->qpk.p, ix->qsi.p,
-                     ix->probe_id.p, ix->probe_d.p, ix->desc.p, ix->lut.p, ix->partial.p};
+                     ix->probe_id.p, ix->probe_d.p, ix->desc.p, ix->lut.p, ix->partial.p, ix->qrot.p, ix->rot_t};
     for (void *p : owned)
         if (p) (void)hipFree(p);
     for (auto &v : ix->ev)
@@ -325,6 +328,11 @@ int load_impl(const ivf_index_desc *d, hipStream_t st, ivf_index *ix)
     if ((rc = dev_copy(ix->const_table, d->const_table, (size_t)256, st))) return rc;
     if ((rc = dev_copy(ix->ids, d->ids, (size_t)N, st))) return rc;
 
+    if (d->rotation) {
+        HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->rot_t), (size_t)D * D * sizeof(float)));
+        transpose_square_kernel<<<dim3((unsigned)((D * D + 255) / 256)), dim3(256), 0, st>>>(d->rotation, D, ix->rot_t);
+        LAUNCHCHK("transpose_square_kernel");
+    }
     HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->cnorm), (size_t)K * sizeof(float)));
     HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->cpk), (size_t)packed_rows(K) * packed_dim(D) * 2 * sizeof(_Float16)));
     HIPCHK(hipMalloc(reinterpret_cast<void **>(&ix->csi), 2 * sizeof(float)));
@@ -502,7 +510,14 @@ int run_search(ivf_index *ix, const SearchArgs &a, const SearchPlan &pl, const L
         }
         if ((rc = mark(3))) return rc;
 
-        lut_kernel<<<dim3((unsigned)n), dim3(256), (size_t)D * sizeof(float), st>>>(Q, D, M, ix->codebook, ws.lut);
+        const float *Qt = Q;                                   // what the lookup tables are built from
+        if (ix->rot_t) {
+            rotate_rows_kernel<<<dim3((unsigned)((n + ROT_ROWS - 1) / ROT_ROWS)), dim3(256), (size_t)ROT_ROWS * D * sizeof(float), st>>>(
+                Q, n, D, ix->rot_t, ws.qrot);
+            LAUNCHCHK("rotate_rows_kernel");
+            Qt = ws.qrot;
+        }
+        lut_kernel<<<dim3((unsigned)n), dim3(256), (size_t)D * sizeof(float), st>>>(Qt, D, M, ix->codebook, ws.lut);
         LAUNCHCHK("lut_kernel");
         if ((rc = mark(4))) return rc;
 
@@ -570,9 +585,9 @@ int search_alloc(ivf_index *ix, const float *queries, int64_t nq, int nprobe, fl
     else if (tile >= 256) tile -= tile % 256;   // whole blocks of the padded row count
     else if (tile >= GT) tile -= tile % GT;
 
-    const SearchPlan pl = plan_search(K, ix->D, ix->M, nprobe, S, k, tile);
+    const SearchPlan pl = plan_search(K, ix->D, ix->M, nprobe, S, k, tile, ix->rot_t != nullptr);
     Buf *bufs[WS_COUNT] = {&ix->dt, &ix->bm, &ix->qn, &ix->qsi, &ix->qpk, &ix->probe_id, &ix->probe_d,
-                           &ix->desc, &ix->lut, &ix->partial};
+                           &ix->desc, &ix->lut, &ix->partial, &ix->qrot};
     for (int i = 0; i < WS_COUNT; ++i)
         if ((rc = ensure(*bufs[i], pl.bytes[i]))) return rc;
     SearchWs ws;
@@ -586,6 +601,7 @@ int search_alloc(ivf_index *ix, const float *queries, int64_t nq, int nprobe, fl
     ws.desc = static_cast<SubDesc *>(ix->desc.p);
     ws.lut = static_cast<float *>(ix->lut.p);
     ws.partial = static_cast<uint64_t *>(ix->partial.p);
+    ws.qrot = static_cast<float *>(ix->qrot.p);
     LdsPlan lds;
     if ((rc = plan_lds(ix, nprobe, k, pl, lds))) return rc;
     const SearchArgs a = {queries, nq, nprobe, k, S, out_ids, out_dists, probe_id_out, probe_d_out, kept_sub_out,
@@ -621,7 +637,7 @@ extern "C" int ivf_search_noalloc(ivf_index *ix, const float *queries, int64_t n
     if (rc || nq == 0) return rc;
     const int S = (int)ivf_num_kept(nprobe, ix->L, prune_frac);
     // the whole batch in one pass: the scratch is carved out of the static array, 256-byte aligned pieces
-    const SearchPlan pl = plan_search(ix->K, ix->D, ix->M, nprobe, S, k, nq);
+    const SearchPlan pl = plan_search(ix->K, ix->D, ix->M, nprobe, S, k, nq, ix->rot_t != nullptr);
     size_t off[WS_COUNT], total = 0;
     for (int i = 0; i < WS_COUNT; ++i) {
         off[i] = total;
@@ -644,6 +660,7 @@ extern "C" int ivf_search_noalloc(ivf_index *ix, const float *queries, int64_t n
     ws.desc = reinterpret_cast<SubDesc *>(base + off[WS_DESC]);
     ws.lut = reinterpret_cast<float *>(base + off[WS_LUT]);
     ws.partial = reinterpret_cast<uint64_t *>(base + off[WS_PARTIAL]);
+    ws.qrot = reinterpret_cast<float *>(base + off[WS_QROT]);
     LdsPlan lds;
     if ((rc = plan_lds(ix, nprobe, k, pl, lds))) return rc;
     const SearchArgs a = {queries, nq, nprobe, k, S, out_ids, out_dists, nullptr, nullptr, nullptr, nullptr, 0, nullptr};
@@ -853,6 +870,8 @@ extern "C" int ivf_encode(const ivf_index_desc *t, const float *x, int64_t n, co
     const size_t cb_bytes = (size_t)256 * t->D * sizeof(float);
     const bool fast = t->pq_codebook && cb_bytes <= 140 * 1024 &&
                       (ds == 4 || ds == 6 || ds == 8 || ds == 12 || ds == 16);
+    if (t->rotation && t->pq_codebook && !fast)
+        return fail(IVF_EINVAL, "a rotation in front of the PQ needs D/M in {4, 6, 8, 12, 16} and a codebook that fits LDS");
     if (!fast) {
         encode_kernel<<<dim3((unsigned)n), dim3(64), (size_t)4 * t->D * sizeof(float), st>>>(
             x, n, t->D, t->M, t->L, out_region, t->centroids, t->nbr, t->alpha, t->cs_dist2, t->pq_codebook,
@@ -862,28 +881,46 @@ extern "C" int ivf_encode(const ivf_index_desc *t, const float *x, int64_t n, co
         return IVF_OK;
     }
     const int64_t chunk = n < (1ll << 20) ? n : (1ll << 20);
-    float *e = nullptr, *mu = nullptr;
+    const int D = t->D;
+    DevTmp e, mu, erot, rt;
     auto body = [&]() -> int {
-        if (!out_residual) HIPCHK(hipMalloc(reinterpret_cast<void **>(&e), (size_t)chunk * t->D * sizeof(float)));
-        HIPCHK(hipMalloc(reinterpret_cast<void **>(&mu), (size_t)chunk * t->D * sizeof(float)));
+        if (!out_residual) HIPCHK(hipMalloc(&e.p, (size_t)chunk * D * sizeof(float)));
+        HIPCHK(hipMalloc(&mu.p, (size_t)chunk * D * sizeof(float)));
+        if (t->rotation) {   // the PQ sees R (x - mu), the per-point constant is taken with R mu
+            HIPCHK(hipMalloc(&erot.p, (size_t)chunk * D * sizeof(float)));
+            HIPCHK(hipMalloc(&rt.p, (size_t)D * D * sizeof(float)));
+            transpose_square_kernel<<<dim3((unsigned)((D * D + 255) / 256)), dim3(256), 0, st>>>(t->rotation, D, static_cast<float *>(rt.p));
+            LAUNCHCHK("transpose_square_kernel");
+        }
         const void *fn = ds == 4 ? (const void *)&pq_encode_kernel<4> : ds == 6 ? (const void *)&pq_encode_kernel<6>
                        : ds == 8 ? (const void *)&pq_encode_kernel<8> : ds == 12 ? (const void *)&pq_encode_kernel<12>
                                                                                  : (const void *)&pq_encode_kernel<16>;
         HIPCHK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)cb_bytes));
+        float *muc = static_cast<float *>(mu.p);
         for (int64_t i0 = 0; i0 < n; i0 += chunk) {
             const int64_t m = n - i0 < chunk ? n - i0 : chunk;
-            float *ec = out_residual ? out_residual + i0 * t->D : e;
-            encode_kernel<<<dim3((unsigned)m), dim3(64), (size_t)4 * t->D * sizeof(float), st>>>(
-                x + i0 * t->D, m, t->D, t->M, t->L, out_region + i0, t->centroids, t->nbr, t->alpha, t->cs_dist2,
-                nullptr, nullptr, out_sub + i0, nullptr, nullptr, nullptr, ec, mu);
+            float *ec = out_residual ? out_residual + i0 * D : static_cast<float *>(e.p);
+            encode_kernel<<<dim3((unsigned)m), dim3(64), (size_t)4 * D * sizeof(float), st>>>(
+                x + i0 * D, m, D, t->M, t->L, out_region + i0, t->centroids, t->nbr, t->alpha, t->cs_dist2,
+                nullptr, nullptr, out_sub + i0, nullptr, nullptr, nullptr, ec, muc);
             LAUNCHCHK("encode_kernel");
+            const float *pe = ec;
+            if (t->rotation) {
+                const unsigned rg = (unsigned)((m + ROT_ROWS - 1) / ROT_ROWS);
+                const size_t rl = (size_t)ROT_ROWS * D * sizeof(float);
+                rotate_rows_kernel<<<dim3(rg), dim3(256), rl, st>>>(ec, m, D, static_cast<float *>(rt.p), static_cast<float *>(erot.p));
+                LAUNCHCHK("rotate_rows_kernel");
+                rotate_rows_kernel<<<dim3(rg), dim3(256), rl, st>>>(muc, m, D, static_cast<float *>(rt.p), muc);
+                LAUNCHCHK("rotate_rows_kernel");
+                pe = static_cast<float *>(erot.p);
+            }
             int64_t grid = (m + 1023) / 1024;
             if (grid > 512) grid = 512;
             uint8_t *oc = out_codes + i0 * t->M;
             uint8_t *ob = out_const_byte ? out_const_byte + i0 : nullptr;
             float *ot = out_const_t ? out_const_t + i0 : nullptr;
 #define IVF_PQ_LAUNCH(DSV)                                                                               \
-    pq_encode_kernel<DSV><<<dim3((unsigned)grid), dim3(1024), cb_bytes, st>>>(ec, mu, m, t->M, t->pq_codebook, \
+    pq_encode_kernel<DSV><<<dim3((unsigned)grid), dim3(1024), cb_bytes, st>>>(pe, muc, m, t->M, t->pq_codebook, \
                                                                                t->const_table, oc, ob, ot)
             if (ds == 4) IVF_PQ_LAUNCH(4);
             else if (ds == 6) IVF_PQ_LAUNCH(6);
@@ -899,11 +936,33 @@ extern "C" int ivf_encode(const ivf_index_desc *t, const float *x, int64_t n, co
     rc = body();
     {
         std::string keep = g_err;
-        (void)hipStreamSynchronize(st);
-        if (e) (void)hipFree(e);
-        if (mu) (void)hipFree(mu);
+        (void)hipStreamSynchronize(st);   // the temporaries are released on return
         g_err = keep;
     }
+    return rc;
+}
+
+extern "C" int ivf_rotate(const float *x, int64_t n, int D, const float *rotation, float *out, void *hip_stream)
+{
+    if (!x || !rotation || !out) return fail(IVF_EINVAL, "NULL argument");
+    if (D < 1 || D > IVF_MAX_D || n < 0 || n >= (1ll << 31)) return fail(IVF_EINVAL, "bad sizes");
+    if (n == 0) return IVF_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    DevTmp rt;
+    HIPCHK(hipMalloc(&rt.p, (size_t)D * D * sizeof(float)));
+    transpose_square_kernel<<<dim3((unsigned)((D * D + 255) / 256)), dim3(256), 0, st>>>(rotation, D, static_cast<float *>(rt.p));
+    int rc = IVF_OK;
+    hipError_t e1 = hipGetLastError();
+    if (e1 != hipSuccess) rc = fail(IVF_EHIP, "launch transpose_square_kernel: %s", hipGetErrorString(e1));
+    if (!rc) {
+        rotate_rows_kernel<<<dim3((unsigned)((n + ROT_ROWS - 1) / ROT_ROWS)), dim3(256), (size_t)ROT_ROWS * D * sizeof(float), st>>>(
+            x, n, D, static_cast<float *>(rt.p), out);
+        e1 = hipGetLastError();
+        if (e1 != hipSuccess) rc = fail(IVF_EHIP, "launch rotate_rows_kernel: %s", hipGetErrorString(e1));
+    }
+    std::string keep = g_err;
+    (void)hipStreamSynchronize(st);
+    g_err = keep;
     return rc;
 }
 

@@ -103,6 +103,44 @@ __global__ __launch_bounds__(BLOCK) void score_prune_kernel(
     if (threadIdx.x == 0 && n_scanned) n_scanned[q] = (int64_t)codes_total;
 }
 
+// Rotation in front of the product quantiser (Section 4: OPQ-compressed displacements, one global
+// rotation): Y[i] = R X[i] for n rows of D floats, with Rt = R transposed ([b][a] = R[a][b]) so
+// that consecutive lanes read consecutive words.  A workgroup takes ROT_ROWS rows into LDS and
+// every thread owns output components a = tid, tid + 256, ...; each component is one chain of
+// fused multiply-adds in the order b = 0 .. D-1.  X and Y may be the same array (a workgroup reads
+// its rows before it writes them).  Dynamic LDS: ROT_ROWS * D floats.
+constexpr int ROT_ROWS = 16;
+
+__global__ __launch_bounds__(256) void rotate_rows_kernel(const float *__restrict__ X, int64_t n, int D,
+                                                          const float *__restrict__ Rt, float *__restrict__ Y)
+{
+    extern __shared__ float xs[];                       // [ROT_ROWS][D]
+    const int64_t r0 = (int64_t)blockIdx.x * ROT_ROWS;
+    const int rows = n - r0 < ROT_ROWS ? (int)(n - r0) : ROT_ROWS;
+    for (int i = threadIdx.x; i < rows * D; i += 256) xs[i] = X[r0 * D + i];
+    __syncthreads();
+    for (int a = threadIdx.x; a < D; a += 256) {
+        float acc[ROT_ROWS];
+#pragma unroll
+        for (int r = 0; r < ROT_ROWS; ++r) acc[r] = 0.f;
+        for (int b = 0; b < D; ++b) {
+            const float w = Rt[(int64_t)b * D + a];
+#pragma unroll
+            for (int r = 0; r < ROT_ROWS; ++r) acc[r] = fmaf(w, xs[r * D + b], acc[r]);   // rows past `rows` hold stale data, never stored
+        }
+        for (int r = 0; r < rows; ++r) Y[(r0 + r) * D + a] = acc[r];
+    }
+}
+
+// out[b][a] = in[a][b] for a D x D matrix
+__global__ __launch_bounds__(256) void transpose_square_kernel(const float *__restrict__ in, int D, float *__restrict__ out)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= D * D) return;
+    const int a = i / D, b = i - a * D;
+    out[b * D + a] = in[i];
+}
+
 // T[q][m][j] = -2 <q_m, r^m_j>; one workgroup of 256 threads per query,
 // thread j owns codeword j of every sub-quantiser.
 __global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ Q, int D, int M,

@@ -36,12 +36,14 @@ def neighbour_table(centroids: torch.Tensor, L: int):
 def build(spec: sd.WorkloadSpec, mix: sd.Mixture, mode: str = "kmeans", chunk: int = 10_000_000,
           n_pq_train: int = 1_000_000, kmeans_iters: int = 10, pq_iters: int = 20, const_iters: int = 20,
           log: Optional[Callable[[str], None]] = None, centroids: Optional[torch.Tensor] = None,
-          alpha_override: Optional[float] = None):
+          alpha_override: Optional[float] = None, rotation: Optional[torch.Tensor] = None):
     """Returns (IndexDesc of flat device tensors, stats dict).
 
     ``centroids`` reuses a region codebook trained earlier (the ablation over L builds several
     indexes on one codebook); ``alpha_override`` forces one scaling factor for every region
-    (0 gives the variant without grouping)."""
+    (0 gives the variant without grouping); ``rotation`` ([D, D], orthogonal) is put in front of
+    the product quantiser (Section 4: OPQ-compressed displacements; learning the rotation itself is
+    not part of this build, any orthogonal matrix may be given)."""
     dev = mix.means.device
     say = log or (lambda s: None)
     stats = {}
@@ -83,10 +85,12 @@ def build(spec: sd.WorkloadSpec, mix: sd.Mixture, mode: str = "kmeans", chunk: i
 
     # PQ codebooks on the displacements of a training subsample, then the scalar table
     n_pq = min(n_pq_train, spec.n_train)
-    desc = B.IndexDesc(cent, nbr, alpha, cs, None, M)
+    desc = B.IndexDesc(cent, nbr, alpha, cs, None, M, rotation=rotation)
     Xp, rp = Xt[:n_pq].contiguous(), reg_t[:n_pq].contiguous()
     _, _, _, _, _, res = B.ivf_encode(desc, Xp, region_in=rp, want_residual=True)
     init_pq = sd.draw_indices(n_pq, 256, "pq-init", dev)
+    if rotation is not None:
+        res = B.ivf_rotate(res, rotation)
     desc.pq_codebook = B.ivf_pq_train(res, M, pq_iters, init_pq)
     _, _, _, _, t = B.ivf_encode(desc, Xp, region_in=rp, want_t=True)
     desc.const_table = B.ivf_lloyd_1d(t, const_iters)

@@ -20,4 +20,5 @@ from .generators import (  # noqa: F401
     draw_points,
     draw_queries,
     draw_indices,
+    random_rotation,
 )

@@ -132,3 +132,14 @@ def draw_indices(n_from: int, n: int, stream: str, device="cpu") -> torch.Tensor
     dev = torch.device(device)
     g = _gen(f"{stream}/{n_from}", 0, dev)
     return torch.randperm(n_from, generator=g, device=dev)[:n].contiguous()
+
+
+def random_rotation(D: int, stream: str = "rotation", device="cpu") -> torch.Tensor:
+    """A seeded random orthogonal D x D matrix (Q of the QR factorisation of a Gaussian matrix,
+    columns signed so that R's diagonal is positive), fp32."""
+    dev = torch.device(device)
+    g = _gen(f"{stream}/{D}", 0, "cpu")
+    a = torch.randn(D, D, generator=g, dtype=torch.float64)
+    q, r = torch.linalg.qr(a)
+    q = q * torch.sign(torch.diagonal(r))[None, :]
+    return q.to(torch.float32).contiguous().to(dev)

@@ -33,6 +33,8 @@ def to_device(ix, with_codes=True):
         d.codes = t(ix.codes)
         d.const_byte = t(ix.const_byte)
         d.ids = t(ix.ids)
+    if getattr(ix, "rotation", None) is not None:
+        d.rotation = t(ix.rotation)
     return d
 
 

@@ -57,3 +57,33 @@ def test_builder_product_is_searchable_and_matches_oracle(mode):
     rep = parity.check_search(ix, Q, spec.nprobe, spec.prune_frac, spec.k, out)
     print(rep)
     rep.assert_ok()
+
+
+def test_builder_with_a_rotation_matches_oracle():
+    """The builder with a seeded random rotation in front of the PQ: its product searches to the
+    oracle's results, and the codes are the oracle's encoder's with that rotation."""
+    print("case: builder with rotation", flush=True)
+    spec = sd.WORKLOADS["tiny"]
+    dev = torch.device("cuda:0")
+    mix = sd.make_mixture(spec.kind, spec.n_mix, spec.D, dev)
+    R = sd.random_rotation(spec.D, device=dev)
+    assert torch.allclose(R @ R.T, torch.eye(spec.D, device=dev), atol=1e-5)
+    desc, stats = index_builder.build(spec, mix, mode="kmeans", chunk=30_000, n_pq_train=20_000, kmeans_iters=4,
+                                      pq_iters=5, rotation=R)
+    ix = download_index(desc, spec)
+    assert ix.rotation is not None
+    Q = sd.draw_queries(mix, spec.nq).cpu().numpy()
+    handle = ivf.ivf_load_index(desc)
+    out = parity.run_gpu_search(handle, Q, spec.nprobe, spec.prune_frac, spec.k)
+    rep = parity.check_search(ix, Q, spec.nprobe, spec.prune_frac, spec.k, out)
+    print(rep)
+    rep.assert_ok()
+    X = torch.cat([sd.draw_points(mix, min(30_000, spec.N - c * 30_000), c, "base")[0]
+                   for c in range((spec.N + 29_999) // 30_000)]).cpu().numpy()
+    pos = np.random.default_rng(2).integers(0, spec.N, 2000)
+    enc = orc.encode(X[ix.ids[pos]], ix.centroids, ix.nbr, ix.alpha, ix.pq_codebook, ix.const_table, rotation=ix.rotation)
+    off = ix.sub_offsets.astype(np.int64)
+    b = enc.region.astype(np.int64) * spec.L + enc.sub
+    inside = (off[b] <= pos) & (pos < off[b + 1])
+    same = inside & (ix.codes[pos] == enc.codes).all(1)
+    assert inside.mean() >= 0.995 and same.mean() >= 0.99
