@@ -21,12 +21,19 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 DESC_BYTES = 16          # one kept-subregion descriptor read by the scan
 
-# HBM bytes per scan launch from rocprofv3 hardware counters (FETCH_SIZE and WRITE_SIZE, each scaled by what
-# the same counter reads for the library's plain 1 GiB copy kernel: 2.0 and 1.0).  Measured offline with the
-# commands in profiles/scan_kernel_<workload>.md; None where no counter run has been made.
-MEASURED_SCAN_TRAFFIC_BYTES = {"deep1b": (5_049_329 * 2.0 + 31_660 * 1.0) * 1024}
-# the same for the stage-1 GEMM (profiles/coarse_gemm_<workload>.md)
-MEASURED_GEMM_TRAFFIC_BYTES = {"deep1b": (5_728_405 * 2.0 + 45_316_072 * 1.0) * 1024}
+# HBM bytes per launch from rocprofv3 hardware counters (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each
+# scaled by what the same counter reads for the library's plain 1 GiB copy kernel: 2.0 and 1.0).  These are
+# readings of separate counter runs of this same command (two `rocprofv3 --pmc` passes cannot run inside a
+# timed benchmark); the profile summary each comes from is named beside it and holds the full commands.
+# None where no counter run has been made for the workload.
+MEASURED_TRAFFIC = {
+    ("scan_kernel", "deep1b"): ((5_049_329 * 2.0 + 31_660 * 1.0) * 1024, "profiles/scan_kernel_deep1b.md"),
+    ("coarse_gemm_sweep_kernel", "deep1b"): ((5_728_405 * 2.0 + 45_316_072 * 1.0) * 1024, "profiles/coarse_gemm_deep1b.md"),
+}
+
+
+def measured_traffic(kernel, workload):
+    return MEASURED_TRAFFIC.get((kernel, workload), (None, None))
 
 
 def log(msg):
@@ -85,23 +92,29 @@ def cpu_baseline(ix, Q, spec, budget_s=20.0):
     return out
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default=os.environ.get("IVF_BENCH_WORKLOAD", "deep1b"))
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--scratch-gib", type=float, default=48.0)
-    ap.add_argument("--nq", type=int, default=0, help="use only the first NQ queries of the workload (latency runs)")
-    ap.add_argument("--calibrate", action="store_true",
-                    help="also run the plain 1 GiB copy kernel (reference for rocprofv3 HBM counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
+def check_sample(ix, Q, spec, ids, dists, n_check=64):
+    """The results that were just timed, on a sample of the queries, against the oracle's whole-path search:
+    counts for the JSON line (selections differ only where the oracle's own fp64 values nearly tie)."""
+    import numpy as np
+    from oracle import ivf_oracle as orc
+    sample = np.unique(np.linspace(0, Q.shape[0] - 1, min(n_check, Q.shape[0])).astype(np.int64))
+    tau = float(np.float32(spec.prune_frac))
+    oi, od, _ = orc.search(ix, Q[sample], spec.nprobe, tau, spec.k)
+    gi, gd = ids[sample], dists[sample]
+    rows_same = int((gi == oi).all(1).sum())
+    # slots holding the same id: compare the distances there
+    same = (gi == oi) & (oi >= 0)
+    rel = np.abs(gd[same].astype(np.float64) - od[same]) / np.maximum(np.abs(od[same]), 1e-30)
+    # ids returned by one side only, per query
+    only = sum(len(set(a.tolist()) ^ set(b.tolist())) // 2 for a, b in zip(gi, oi))
+    return {"queries_checked": int(len(sample)), "rows_identical": rows_same,
+            "slots_identical": int(same.sum()), "slots_total": int((oi >= 0).sum()),
+            "ids_in_one_result_only": int(only),
+            "max_rel_dist_err_on_identical_slots": float(rel.max()) if rel.size else 0.0}
 
+
+def measure(args, workload, nq=0, with_oracle=True, with_cpu_baseline=True, calibrate=False):
+    """Builds the workload's index on the device, times `args.steps` passes and returns the result object."""
     import torch
     import synthdata as sd
     import paper_1802_02422_amd as ivf
@@ -109,10 +122,10 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
-    spec = sd.WORKLOADS[args.workload]
-    if args.nq:
+    spec = sd.WORKLOADS[workload]
+    if nq:
         import dataclasses
-        spec = dataclasses.replace(spec, nq=min(args.nq, spec.nq))
+        spec = dataclasses.replace(spec, nq=min(nq, spec.nq))
     ivf.load_library()
 
     t0 = time.time()
@@ -123,7 +136,7 @@ def main():
     log(f"index built in {time.time() - t0:.1f}s ({mode}); stats {stats}")
 
     host_ix = None
-    if not args.no_cpu_baseline:
+    if with_oracle:
         host_ix = download_index(desc, spec)
         log(f"index downloaded to host {time.time() - t0:.1f}s")
     handle = ivf.ivf_load_index(desc)
@@ -143,14 +156,20 @@ def main():
     for _ in range(args.warmup):
         ivf.ivf_search(handle, Q, spec.nprobe, spec.prune_frac, spec.k, out_ids, out_d)
     torch.cuda.synchronize()
-    ivf.ivf_profile_enable(handle, True)
-    ivf.ivf_profile_read(handle)
-    torch.cuda.synchronize()
+    # the headline time: exactly `steps` passes, nothing but the library's launches in the timed region
     t1 = time.perf_counter()
     for _ in range(args.steps):
         ivf.ivf_search(handle, Q, spec.nprobe, spec.prune_frac, spec.k, out_ids, out_d)
     torch.cuda.synchronize()
     t2 = time.perf_counter()
+    # the per-stage and per-kernel times: the same `steps` passes again with HIP events recorded on the stream
+    # around every stage inside the library (the events cost a few microseconds per stage, which matters only
+    # for the latency workloads)
+    ivf.ivf_profile_enable(handle, True)
+    ivf.ivf_profile_read(handle)
+    for _ in range(args.steps):
+        ivf.ivf_search(handle, Q, spec.nprobe, spec.prune_frac, spec.k, out_ids, out_d)
+    torch.cuda.synchronize()
     stage_ms, passes = ivf.ivf_profile_read(handle)
     ivf.ivf_profile_enable(handle, False)
 
@@ -171,7 +190,7 @@ def main():
     gemm_achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
 
     copy_gbs = None
-    if args.calibrate:
+    if calibrate:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         b = torch.empty_like(a)
         ivf.ivf_copy_bytes(b, a)
@@ -202,7 +221,8 @@ def main():
                       "accumulated in fp32 on the matrix cores, same accuracy as fp32",
         "roofline": {"kernel": "scan_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_SCAN_TRAFFIC_BYTES.get(spec.name),
+                     "traffic": measured_traffic("scan_kernel", spec.name)[0],
+                     "traffic_source": measured_traffic("scan_kernel", spec.name)[1],
                      "launches": scan_launches, "avg_launch_ms": scan_ms, "algorithmic_bytes_per_launch": algo_bytes,
                      # the same with 12 instead of this library's 16 bytes counted per descriptor
                      "frac_at_12B_per_descriptor": (algo_bytes - 4 * spec.nq * S * args.steps / max(scan_launches, 1))
@@ -210,14 +230,58 @@ def main():
         # the longest stage, bound by its stores; timed by events around packing + GEMM (packing: a few us)
         "roofline_coarse_gemm": {"kernel": gemm_kernel, "bound": "hbm", "achieved": gemm_achieved,
                                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_achieved / HBM_PEAK_GBS,
-                                 "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(spec.name),
+                                 "traffic": measured_traffic(gemm_kernel, spec.name)[0],
+                                 "traffic_source": measured_traffic(gemm_kernel, spec.name)[1],
                                  "launches": passes, "avg_launch_ms": gemm_ms,
                                  "algorithmic_bytes_per_launch": gemm_bytes},
     }
     if copy_gbs is not None:
         result["copy_kernel_gbs_read_plus_write"] = copy_gbs
     if host_ix is not None:
-        result["cpu_baseline"] = cpu_baseline(host_ix, Q.cpu().numpy(), spec)
+        Qh = Q.cpu().numpy()
+        result["checked_against_oracle"] = check_sample(host_ix, Qh, spec, out_ids.cpu().numpy(), out_d.cpu().numpy())
+        log(f"sample check: {result['checked_against_oracle']}")
+        if with_cpu_baseline:
+            result["cpu_baseline"] = cpu_baseline(host_ix, Qh, spec)
+    ivf.ivf_free_index(handle)
+    del handle, desc
+    torch.cuda.empty_cache()
+    return result
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=os.environ.get("IVF_BENCH_WORKLOAD", "deep1b"))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--scratch-gib", type=float, default=48.0)
+    ap.add_argument("--nq", type=int, default=0, help="use only the first NQ queries of the workload (latency runs)")
+    ap.add_argument("--all", action="store_true",
+                    help="after the headline workload also measure the other workloads of the benchmark definition "
+                         "(reported inside the same JSON line as other_workloads)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run the plain 1 GiB copy kernel (reference for rocprofv3 HBM counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    result = measure(args, args.workload, args.nq, with_oracle=not args.no_cpu_baseline,
+                     with_cpu_baseline=not args.no_cpu_baseline, calibrate=args.calibrate)
+    if args.all:
+        # the other workloads of the benchmark definition, each with its stage split and the scan's roofline
+        # fraction (no CPU baseline; the sample check against the oracle stays on)
+        others = []
+        for name, nq in (("deep10m", 0), ("sift10m", 0), ("deep100m", 1), ("deep100m", 64), ("tiny", 0)):
+            if name == args.workload and nq == args.nq:
+                continue
+            r = measure(args, name, nq, with_oracle=not args.no_cpu_baseline, with_cpu_baseline=False)
+            others.append({k_: r[k_] for k_ in ("value", "unit", "ms_per_step", "config", "codes_scanned_per_s",
+                                                "stage_ms_per_step", "roofline", "checked_against_oracle") if k_ in r})
+        result["other_workloads"] = others
     print(json.dumps(result), flush=True)
 
 
