@@ -12,8 +12,12 @@
  *     (NULL = the default stream); calls return without waiting for it unless
  *     stated otherwise.
  *   - Return value 0 = success, negative = error (see IVF_E*).  Nothing throws
- *     across this boundary.  On error no output buffer has been written and
- *     ivf_last_error() describes the failure (thread-local, host string).
+ *     across this boundary.  ivf_last_error() describes the failure
+ *     (thread-local, host string).  Argument errors (IVF_EINVAL) are found
+ *     before anything is launched: no output buffer has been written.  An
+ *     IVF_ENOMEM / IVF_EHIP in the middle of a batch that is processed in
+ *     several passes (see ivf_set_scratch_limit) leaves the outputs of the
+ *     passes already enqueued written and the rest untouched.
  *   - Row-major everywhere.  D is a multiple of 4 and of M; M is 8 or 16.
  */
 #ifndef IVF_GP_H
@@ -77,11 +81,25 @@ typedef struct ivf_index_desc {
 /*
  * Build a search handle from a trained + encoded index.  The library makes its
  * own device copy of everything it needs (codes and constant bytes are
- * re-laid out into 64-byte aligned per-subregion blocks; the Eq. (7) constant
- * -alpha(1-alpha)||c - s_l||^2 is tabulated per (region, neighbour), "precomputed
- * offline and stored explicitly for each neighboring centroid"), so the
- * caller may free its arrays once the call has returned.  Runs on `hip_stream` and
- * waits for it.  codes / const_byte / ids / sub_offsets may not be NULL here.
+ * re-laid out into 16-byte aligned per-subregion blocks; the Eq. (7) constant
+ * -alpha(1-alpha)||c - s_l||^2 is tabulated per (region, neighbour), as Section
+ * 3.2 "Subregions pruning" prescribes), so the caller may free its arrays once
+ * the call has returned; while the call runs both copies exist (there is no
+ * borrowing mode: the record blocks are a different layout from the caller's
+ * arrays).  Runs on `hip_stream` and waits for it.  codes / const_byte / ids /
+ * sub_offsets may not be NULL here.
+ * Dynamic range: the centroid table is packed for the matrix units with ONE
+ * power-of-two scale for the whole table (queries: one per row), as a high and
+ * a low fp16 half per component.  A component within 2^-17 of the table's
+ * largest magnitude keeps 22 significant bits; a smaller one is held to an
+ * absolute 2^-39 of that largest magnitude (its low half is an fp16
+ * subnormal), and one below 2^-39 of it vanishes.  The resulting error of a
+ * distance is at most 2^-38 * max|c_i| * ||q||_1, far inside the bound the
+ * stage-1 distances are tested against, 16 u (||q||^2 + max||c||^2) with
+ * u = 2^-24; but that bound is absolute in the largest centroid norm: rows
+ * many orders of magnitude smaller than the largest row are resolved to that
+ * absolute accuracy (as with any evaluation of ||q||^2 - 2<q,c> + ||c||^2 in
+ * fp32), not to a relative accuracy of their own size.
  */
 int ivf_load_index(const ivf_index_desc *desc, void *hip_stream, ivf_index **out);
 

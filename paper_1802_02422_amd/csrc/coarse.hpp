@@ -280,7 +280,9 @@ __device__ __forceinline__ void emit_block(const floatx16 (&acc)[2], float qr, f
     } else if (h == 0 && (!EDGE || (q < nq && blk < nb))) {
         bm[q * nb + blk] = m;
     }
-    // through the staging area, SROWS query rows at a time (the lanes of the other rows sit a pass out)
+    // through the staging area, SROWS query rows at a time (the lanes of the other rows sit a pass out).
+    // The interior path issues exactly (32 / SROWS) * (SROWS / 4) store instructions: the sweep kernel's
+    // hand-counted waits depend on that number.
 #pragma unroll
     for (int pass = 0; pass < 32 / SROWS; ++pass) {
         if (SROWS == 32 || (l32 / SROWS) == pass) {
@@ -410,7 +412,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     constexpr int PD = RING - 1;
     constexpr int Dp = STAGES * DK;
     constexpr int SLOT = GT * ROWF;                        // floats per ring buffer: 128 rows x 64 bytes
-    constexpr int EPI_STORES = 16;                         // distance stores of an interior epilogue (a lower bound of its stores)
+    // Distance stores of one tile's interior epilogue per wavefront: two emit_block<false, SROWS = 16, true>
+    // calls, each 32 / SROWS passes of SROWS / 4 store instructions for its two 32-centroid halves' 64
+    // columns (one instruction covers 4 rows x 256 bytes).  The waits below count on exactly this number
+    // of vector-memory operations between a copy and its consumer: emit_block's store count is part of
+    // this kernel's contract.
+    constexpr int EPI_SROWS = 16;
+    constexpr int EPI_STORES = 2 * (32 / EPI_SROWS) * (EPI_SROWS / 4);
+    static_assert(EPI_STORES == 16, "the vmcnt immediates of the sweep loop assume 16 epilogue stores per tile");
     __shared__ __attribute__((aligned(16))) float ring0[SLOT];
     __shared__ __attribute__((aligned(16))) float ring1[SLOT];
     __shared__ __attribute__((aligned(16))) float ring2[SLOT];
@@ -587,7 +596,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         const float *cnw = cns[t & 1] + wc;
 #pragma unroll
         for (int i = 0; i < 2; ++i)
-            emit_block<false, 16, true>(acc[i], qr[i], m2[i], cnw, stage, q0 + wq + i * 32, nq, c0 + wc, K, Dt, ldt, bm, nb,
+            emit_block<false, EPI_SROWS, true>(acc[i], qr[i], m2[i], cnw, stage, q0 + wq + i * 32, nq, c0 + wc, K, Dt, ldt, bm, nb,
                                         &bmbuf[(wq + i * 32) * BMLD + ((t - t_begin) % BMC) * 2 + (wave & 1)], BMLD);
 #pragma unroll
         for (int i = 0; i < 2; ++i)

@@ -5,7 +5,10 @@
 
 namespace ivf {
 
-constexpr int BLK_ALIGN = 16;   // a 16-byte code is one aligned 128-bit load; tighter than the fetch granularity on purpose: measured fastest
+#ifndef IVF_BLK_ALIGN
+#define IVF_BLK_ALIGN 16
+#endif
+constexpr int BLK_ALIGN = IVF_BLK_ALIGN;   // a 16-byte code is one aligned 128-bit load; tighter than the fetch granularity on purpose: measured fastest
 
 // cst[r][l] = -alpha_r (1 - alpha_r) ||c_r - s_l||^2
 __global__ __launch_bounds__(256) void cst_kernel(const float *__restrict__ alpha,

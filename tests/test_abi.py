@@ -52,3 +52,81 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(b, "_LIB_PATH", "/nonexistent/libivf_gp.so")
     with pytest.raises(b.IvfError):
         b.load_library()
+
+
+def _built_library():
+    import paper_1802_02422_amd as ivf
+    if not os.path.exists(ivf.library_path()):
+        from paper_1802_02422_amd.build import build_library
+        build_library()
+    return ivf.library_path()
+
+
+def test_c_program_against_the_header(tmp_path):
+    """A C99 program compiled against include/ivf_gp.h and linked with the library calls the
+    host-only entry point and the argument-error path of every other entry point through the real
+    prototypes (no GPU needed: argument errors return before any device work)."""
+    import subprocess
+    lib = _built_library()
+    exe = tmp_path / "abi_check"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           os.path.join(ROOT, "tests", "abi", "abi_check.c"), "-o", str(exe),
+                           lib, "-Wl,-rpath," + os.path.dirname(lib), "-Wl,-rpath,/opt/rocm/lib"])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0 and "abi ok" in out.stdout, out.stdout + out.stderr
+
+
+def _header_prototypes():
+    """name -> list of parameter kinds ('ptr', 'i64', 'i32', 'f32') and the return kind, from the header."""
+    text = open(os.path.join(ROOT, "include", "ivf_gp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    protos = {}
+    for ret, name, params in re.findall(r"\b(int64_t|int|void|const char \*)\s*(ivf_[a-z_0-9]+)\s*\(([^)]*)\)\s*;", text):
+        kinds = []
+        for p in [q.strip() for q in params.split(",")]:
+            if p in ("void", ""):
+                continue
+            if "*" in p:
+                kinds.append("ptr")
+            elif p.startswith("int64_t"):
+                kinds.append("i64")
+            elif p.startswith("float"):
+                kinds.append("f32")
+            elif p.startswith(("int ", "int32_t")):
+                kinds.append("i32")
+            else:
+                raise AssertionError(f"unrecognised parameter {p!r} of {name}")
+        protos[name] = (kinds, ret.strip())
+    return protos
+
+
+def test_ctypes_signatures_follow_the_header():
+    """The hand-written argtypes of the binding against the header's prototypes, parameter by parameter."""
+    import ctypes as C
+    import paper_1802_02422_amd as ivf
+    _built_library()
+    lib = ivf.load_library()
+    protos = _header_prototypes()
+    assert set(protos) == set(declared_symbols())
+    def kind(t):
+        if t in (C.c_int64,):
+            return "i64"
+        if t in (C.c_int, C.c_int32):
+            return "i32"
+        if t is C.c_float:
+            return "f32"
+        if t is C.c_void_p or t is C.c_char_p or hasattr(t, "contents") or getattr(t, "_type_", None) is not None:
+            return "ptr"
+        raise AssertionError(t)
+    for name, (kinds, ret) in protos.items():
+        fn = getattr(lib, name)
+        if name == "ivf_last_error":
+            assert fn.restype is C.c_char_p
+            continue
+        assert fn.argtypes is not None, f"{name}: the binding declares no argtypes"
+        got = []
+        for t in fn.argtypes:
+            got.append("ptr" if (isinstance(t, type) and issubclass(t, C._Pointer)) else kind(t))
+        assert got == kinds, (name, got, kinds)
+        if ret == "int64_t":
+            assert fn.restype is C.c_int64, name

@@ -48,11 +48,11 @@ def test_coarse_distances_within_fp32_bound_for_all_kernel_variants(D, K, nq):
     """Shapes that reach every variant of the coarse kernel (small batch, generic tile with a
     padded width, swept tiles with a partial last query tile, with fewer tiles than one write-out
     of the block minima covers and with rows of block minima that are not 16-byte aligned), rows of very different
-    magnitude, exact duplicates: every returned distance is within 16 u (|q|^2 + max |c|^2) of
+    magnitude (centroid rows up to 2^16 apart under the one scale of the table), exact duplicates: every returned distance is within 16 u (|q|^2 + max |c|^2) of
     the fp64 value, and the P returned regions are the exact ones up to ties inside that bound."""
     print("case: coarse variants", D, K, nq, flush=True)
     rng = np.random.default_rng(1000 * D + K + nq)
-    C = rng.standard_normal((K, D)) * np.exp2(rng.integers(-6, 1, size=(K, 1)))
+    C = rng.standard_normal((K, D)) * np.exp2(rng.integers(-16, 1, size=(K, 1)))     # rows 2^-16 .. 2^0 apart
     Q = rng.standard_normal((nq, D)) * np.exp2(rng.integers(-8, 9, size=(nq, 1)))
     Q[0] = C[K // 2]                                     # a query that is a centroid: distance 0
     C, Q = C.astype(np.float32), Q.astype(np.float32)
