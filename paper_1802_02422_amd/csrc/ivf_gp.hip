@@ -440,6 +440,7 @@ int plan_lds(const ivf_index *ix, int P, int k, const SearchPlan &pl, LdsPlan &l
     l.scan = (size_t)SCAN_WAVES * pool_capacity(k) * sizeof(uint64_t);   // dynamic part: the pools
     l.merge = ((size_t)pl.merge_n + pl.merge_pow2) * sizeof(uint64_t);
     l.sp = (size_t)(PL + 3 * P) * sizeof(uint32_t);
+    if (l.sp < (size_t)ix->D * sizeof(float)) l.sp = (size_t)ix->D * sizeof(float);   // the table workgroups hold a query
     if (l.sp > 154 * 1024)   // one workgroup holds a query's scores in the 160 KB of LDS, beside 5 KB of static data
         return fail(IVF_EINVAL, "nprobe*L + 3*nprobe = %lld words exceed the LDS of one workgroup", (long long)(PL + 3 * P));
     if (l.sp > 48 * 1024) {
@@ -492,15 +493,22 @@ int run_search(ivf_index *ix, const SearchArgs &a, const SearchPlan &pl, const L
 
         int64_t *ks = a.kept_sub_out ? a.kept_sub_out + q0 * S : nullptr;
         int64_t *ns = a.n_scanned_out ? a.n_scanned_out + q0 : nullptr;
-        if (PL > 16384)
-            score_prune_kernel<1024, 8><<<dim3((unsigned)n), dim3(1024), lds.sp, st>>>(
-                ws.dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, ws.desc, ks, ns);
-        else if (PL > 4096)
-            score_prune_kernel<1024, 4><<<dim3((unsigned)n), dim3(1024), lds.sp, st>>>(
-                ws.dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, ws.desc, ks, ns);
-        else
-            score_prune_kernel<256, 4><<<dim3((unsigned)n), dim3(256), lds.sp, st>>>(
-                ws.dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, ws.desc, ks, ns);
+        const float *Qt = Q;                                   // what the lookup tables are built from
+        if (ix->rot_t) {
+            rotate_rows_kernel<<<dim3((unsigned)((n + ROT_ROWS - 1) / ROT_ROWS)), dim3(256), (size_t)ROT_ROWS * D * sizeof(float), st>>>(
+                Q, n, D, ix->rot_t, ws.qrot);
+            LAUNCHCHK("rotate_rows_kernel");
+            Qt = ws.qrot;
+        }
+        // stages 2-3 (one workgroup per query) and stage 4 (one more workgroup per query) in one launch
+#define IVF_SP_LAUNCH(BLK, MV)                                                                                     \
+    score_prune_kernel<BLK, MV><<<dim3((unsigned)(2 * n)), dim3(BLK), lds.sp, st>>>(                                \
+        ws.dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, ws.desc, ks, ns, n, Qt, \
+        D, M, ix->codebook, ws.lut)
+        if (PL > 16384) IVF_SP_LAUNCH(1024, 8);
+        else if (PL > 4096) IVF_SP_LAUNCH(1024, 4);
+        else IVF_SP_LAUNCH(256, 4);
+#undef IVF_SP_LAUNCH
         LAUNCHCHK("score_prune_kernel");
         if (a.budget > 0) {
             const uint32_t R = a.budget > 0xFFFFFFFFll ? 0xFFFFFFFFu : (uint32_t)a.budget;
@@ -509,17 +517,7 @@ int run_search(ivf_index *ix, const SearchArgs &a, const SearchPlan &pl, const L
             LAUNCHCHK("budget_cut_kernel");
         }
         if ((rc = mark(3))) return rc;
-
-        const float *Qt = Q;                                   // what the lookup tables are built from
-        if (ix->rot_t) {
-            rotate_rows_kernel<<<dim3((unsigned)((n + ROT_ROWS - 1) / ROT_ROWS)), dim3(256), (size_t)ROT_ROWS * D * sizeof(float), st>>>(
-                Q, n, D, ix->rot_t, ws.qrot);
-            LAUNCHCHK("rotate_rows_kernel");
-            Qt = ws.qrot;
-        }
-        lut_kernel<<<dim3((unsigned)n), dim3(256), (size_t)D * sizeof(float), st>>>(Qt, D, M, ix->codebook, ws.lut);
-        LAUNCHCHK("lut_kernel");
-        if ((rc = mark(4))) return rc;
+        if ((rc = mark(4))) return rc;   // (the lookup tables are built inside the launch above)
 
         if (M == 16)
             scan_kernel<16><<<dim3((unsigned)(n * pl.nsplit)), dim3(SCAN_BLOCK), lds.scan, st>>>(

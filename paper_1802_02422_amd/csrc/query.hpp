@@ -14,6 +14,25 @@ struct SubDesc {
     float base;      // distance from the query to the subcentroid
 };
 
+// T[q][m][j] = -2 <q_m, r^m_j> (Eq. (6)) for one query by one workgroup of BLOCK threads: the query
+// in LDS (qs, D floats), every thread one (sub-quantiser, codeword) pair at a time, each entry one
+// chain of fused multiply-adds over the block's dimensions.
+template <int BLOCK>
+__device__ __forceinline__ void lut_body(const float *__restrict__ Qrow, int D, int M,
+                                         const float *__restrict__ codebook, float *__restrict__ Tq, float *qs)
+{
+    const int ds = D / M;
+    for (int i = threadIdx.x; i < D; i += BLOCK) qs[i] = Qrow[i];
+    __syncthreads();
+    for (int e = threadIdx.x; e < M * 256; e += BLOCK) {
+        const int m = e >> 8;
+        const float *cw = codebook + (int64_t)e * ds;
+        float s = 0.f;
+        for (int i = 0; i < ds; ++i) s = fmaf(qs[m * ds + i], cw[i], s);
+        Tq[e] = -2.f * s;
+    }
+}
+
 // Stages 2 and 3 fused, one workgroup per query.
 // Stage 2 (Eq. (7)): score[p][l] = (1-a) D[q][r] + a D[q][nbr[r][l]] + cst[r][l], r = probe_id[q][p],
 // cst[r][l] = -a(1-a)||c_r - s_l||^2 tabulated at load time.  The neighbour distances are gathered from
@@ -27,17 +46,28 @@ struct SubDesc {
 // reads of the subregion table of four positions in flight per thread (filled item by item as
 // they were selected, every read of that table was waited for before the next was issued).
 // Dynamic LDS: P*L keys + P probe ids + P probe distances + P alphas.  P*L <= 4 * MAXV * BLOCK.
+// Stage 4 rides along: the grid has 2 nq workgroups, and workgroup nq + q builds query q's lookup
+// table (lut_body, from Qt = the queries, rotated if the index has a rotation) while the first nq
+// gather and select; the two halves share nothing, and the table work hides under the gathers.
+// Dynamic LDS must also hold D floats.
 template <int BLOCK, int MAXV>
 __global__ __launch_bounds__(BLOCK) void score_prune_kernel(
     const float *__restrict__ Dt, int64_t ldt, int64_t K, const int32_t *__restrict__ probe_id,
     const float *__restrict__ probe_d, int P, int L, const int32_t *__restrict__ nbr,
     const float *__restrict__ cst, const float *__restrict__ alpha, int S,
     const uint4 *__restrict__ sub_info,
-    SubDesc *__restrict__ desc, int64_t *__restrict__ kept_sub, int64_t *__restrict__ n_scanned)
+    SubDesc *__restrict__ desc, int64_t *__restrict__ kept_sub, int64_t *__restrict__ n_scanned,
+    int64_t nq, const float *__restrict__ Qt, int D, int M, const float *__restrict__ codebook,
+    float *__restrict__ lut)
 {
     __shared__ SelectShared sh;
     __shared__ unsigned long long codes_total;
     extern __shared__ __attribute__((aligned(16))) uint32_t dyn[];
+    if ((int64_t)blockIdx.x >= nq) {   // (uniform) a table workgroup
+        const int64_t ql = (int64_t)blockIdx.x - nq;
+        lut_body<BLOCK>(Qt + ql * D, D, M, codebook, lut + ql * (int64_t)M * 256, reinterpret_cast<float *>(dyn));
+        return;
+    }
     const int PL = P * L;
     uint32_t *keys = dyn;
     int32_t *pid = reinterpret_cast<int32_t *>(dyn + PL);
@@ -139,25 +169,6 @@ __global__ __launch_bounds__(256) void transpose_square_kernel(const float *__re
     if (i >= D * D) return;
     const int a = i / D, b = i - a * D;
     out[b * D + a] = in[i];
-}
-
-// T[q][m][j] = -2 <q_m, r^m_j>; one workgroup of 256 threads per query,
-// thread j owns codeword j of every sub-quantiser.
-__global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ Q, int D, int M,
-                                                  const float *__restrict__ codebook,
-                                                  float *__restrict__ T)
-{
-    extern __shared__ float qs[];
-    const int64_t q = blockIdx.x;
-    const int j = threadIdx.x, ds = D / M;
-    for (int i = j; i < D; i += 256) qs[i] = Q[q * D + i];
-    __syncthreads();
-    for (int m = 0; m < M; ++m) {
-        const float *cw = codebook + ((int64_t)m * 256 + j) * ds;
-        float s = 0.f;
-        for (int i = 0; i < ds; ++i) s = fmaf(qs[m * ds + i], cw[i], s);
-        T[(q * M + m) * 256 + j] = -2.f * s;
-    }
 }
 
 }  // namespace ivf

@@ -60,7 +60,7 @@ class Report:
         self.counts = {}
         self.max_gap = {}
         self.max_rel = 0.0       # beyond the absolute floor of the tolerance (what the bar applies to)
-        self.max_rel_raw = 0.0   # plain |gpu - oracle| / |oracle| wherever |oracle| exceeds the absolute floor
+        self.max_rel_raw = 0.0   # plain |gpu - oracle| / |oracle| wherever |oracle| exceeds 1e4 x the absolute floor
 
     def add(self, stage, kind, gap=0.0):
         self.counts.setdefault(stage, {"exact": 0, "near": 0, "mismatch": 0})[kind] += 1
@@ -148,8 +148,11 @@ def check_topk(ix, st, out, at, rep):
             e = np.abs(g_d[q, :n_valid].astype(np.float64) - dg)
             rel = (np.maximum(e - at[q], 0) / np.maximum(np.abs(dg), 1e-30)).max()
             rep.max_rel = max(rep.max_rel, float(rel))
-            # the plain bar: relative error wherever the oracle's distance stands clear of the absolute floor
-            clear = np.abs(dg) > at[q]
+            # the plain bar, 1e-4 relative with no allowance, wherever it is attainable in fp32: the estimate
+            # is a sum of O(||q||^2 + ||c||^2) terms and carries an absolute error of the order of the floor
+            # `at`, so it can be 1e-4-relative only for distances above 1e4 * at (every distance of the
+            # benchmark workloads is: they are ~5e5 * at); below that the bar above (with the floor) applies
+            clear = np.abs(dg) > 1e4 * at[q]
             if clear.any():
                 rep.max_rel_raw = max(rep.max_rel_raw, float((e[clear] / np.abs(dg[clear])).max()))
             assert (np.diff(g_d[q, :n_valid]) >= 0).all(), "returned distances not ascending"
