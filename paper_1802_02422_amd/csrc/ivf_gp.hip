@@ -224,7 +224,10 @@ SearchPlan plan_search(int64_t K, int D, int M, int P, int S, int k, int64_t til
     pl.tile = tile;
     pl.S = S;
     // workgroups per query in the scan: fill the chip when the batch is small
-    int nsplit = (int)((2048 + tile - 1) / tile);
+#ifndef IVF_SCAN_WG_TARGET
+#define IVF_SCAN_WG_TARGET 2048
+#endif
+    int nsplit = (int)((IVF_SCAN_WG_TARGET + tile - 1) / tile);
     if (nsplit > 64) nsplit = 64;
     if (nsplit > (S + 15) / 16) nsplit = (S + 15) / 16;
     while (nsplit > 1 && (int64_t)nsplit * SCAN_WAVES * k > 8192) --nsplit;
