@@ -114,7 +114,7 @@ def check_stored_points_against_oracle_encoder(spec, mix, mode, desc, ix, n_chec
         assert abs(d_st - d_or) <= 1e-5 * max(d_or, 1.0), (i, d_st, d_or)
 
 
-def full_size_case(name, n_sample, extra_batches=()):
+def full_size_case(name, n_sample, extra_batches=(), budget=0, n_budget=32):
     spec = sd.WORKLOADS[name]
     dev = torch.device("cuda:0")
     mix = sd.make_mixture(spec.kind, spec.n_mix, spec.D, dev)
@@ -142,6 +142,18 @@ def full_size_case(name, n_sample, extra_batches=()):
     rep = parity.check_search(ix, Q.cpu().numpy()[sample], spec.nprobe, spec.prune_frac, spec.k, out)
     print(name, rep, flush=True)
     rep.assert_ok(max_near_frac=0.1)
+    if budget:                                               # the candidate-budget entry point at full size
+        sq = torch.from_numpy(sample[:n_budget]).to(dev)
+        Qs = Q[sq].contiguous()
+        so = ivf.ivf_search_stages(handle, Qs, spec.nprobe, spec.prune_frac, spec.k)
+        bo = ivf.ivf_search_budget(handle, Qs, spec.nprobe, spec.prune_frac, budget, spec.k)
+        torch.cuda.synchronize()
+        so = {n: v.cpu().numpy() for n, v in so.items()}
+        bo = {n: v.cpu().numpy() for n, v in bo.items()}
+        rep = parity.check_search_budget(ix, Qs.cpu().numpy(), spec.nprobe, spec.prune_frac, budget, spec.k, so, bo)
+        print(name, "budget", budget, rep, flush=True)
+        rep.assert_ok(max_near_frac=0.1)
+        assert (bo["n_scanned"] >= np.minimum(budget, so["n_scanned"])).all()
     for nb in extra_batches:                                 # other batch sizes of the same workload
         o2 = ivf.ivf_search_stages(handle, Q[:nb].contiguous(), spec.nprobe, spec.prune_frac, spec.k)
         torch.cuda.synchronize()
@@ -154,7 +166,7 @@ def full_size_case(name, n_sample, extra_batches=()):
 
 def test_full_size_deep10m_sampled_queries():
     print("case: deep10m full size", flush=True)
-    full_size_case("deep10m", 128)
+    full_size_case("deep10m", 128, budget=1000)
 
 
 def test_full_size_sift10m_sampled_queries():
@@ -169,7 +181,7 @@ def test_full_size_deep100m_latency_batches():
 
 def test_full_size_deep1b_sampled_queries():
     print("case: deep1b full size", flush=True)
-    full_size_case("deep1b", 256)
+    full_size_case("deep1b", 256, budget=30000)
 
 
 @pytest.mark.parametrize("mode", ["zero", "one", "mixed"])
