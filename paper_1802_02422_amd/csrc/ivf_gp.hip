@@ -223,12 +223,12 @@ SearchPlan plan_search(int64_t K, int D, int M, int P, int S, int k, int64_t til
     SearchPlan pl;
     pl.tile = tile;
     pl.S = S;
-    // workgroups per query in the scan: fill the chip when the batch is small
-#ifndef IVF_SCAN_WG_TARGET
-#define IVF_SCAN_WG_TARGET 2048
-#endif
-    int nsplit = (int)((IVF_SCAN_WG_TARGET + tile - 1) / tile);
-    if (nsplit > 64) nsplit = 64;
+    // workgroups per query in the scan: fill the chip when the batch is small, but with at most 8 per
+    // query: every workgroup hands 4 k candidates to the final k-select, whose time grows with them
+    // faster than the scan's shrinks (one query on the 100M-point workload, scan + k-select in us:
+    // 17 + 9 with 2 workgroups, 12 + 9 with 4, 10.5 + 10 with 8, 10 + 12 / 14 / 20 with 16 / 32 / 64)
+    int nsplit = (int)((2048 + tile - 1) / tile);
+    if (nsplit > 8) nsplit = 8;
     if (nsplit > (S + 15) / 16) nsplit = (S + 15) / 16;
     while (nsplit > 1 && (int64_t)nsplit * SCAN_WAVES * k > 8192) --nsplit;
     if (nsplit < 1) nsplit = 1;
