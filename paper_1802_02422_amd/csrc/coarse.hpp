@@ -589,6 +589,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
         {   // norms of the next tile (index clamped past the end).  The load is hidden from the compiler,
             // which would otherwise drain the whole queue, stores included, where the value is used.
+            // (cn_next's register is written when the load returns: nothing may read or move it before the
+            // explicit wait at its use; the parity tests of this kernel are what checks a new build.)
             const int64_t cnx = c0 + GT + (tid & (GT - 1));
             const float *pn = cn + (cnx < K ? cnx : K - 1);
             asm volatile("global_load_dword %0, %1, off" : "=v"(cn_next) : "v"(pn) : "memory");
