@@ -209,9 +209,25 @@ int64_t ivf_num_kept(int nprobe, int L, float prune_frac);
  * distances.  Used for query assignment, for assigning points to regions
  * (P = 1) and for the neighbour table NN_L (Eq. (2)).  Allocates and frees its
  * own scratch (waits for the stream).
+ * P = 1 (also inside ivf_encode and ivf_kmeans) runs in two passes: a
+ * reduced-precision product (the fp16 leading halves of the operands, a third
+ * of the matrix work) with a proven error bound lists for every row the
+ * centroids that may be its nearest, and exact fp32 distances of the listed
+ * pairs decide, ties to the smaller id; a chunk of rows whose list overflows
+ * is redone by the one-pass full-precision kernel.  The result is the exact
+ * nearest centroid either way.
  */
 int ivf_coarse_topk(const float *centroids, int64_t K, int D, const float *x, int64_t nq, int P,
                     int32_t *out_id, float *out_d, void *hip_stream);
+
+/*
+ * How the chunks (up to 2^20 rows each) of all nearest-centroid assignments of
+ * this process were decided so far (out: two values, host memory): out[0] by the shortlist and the exact
+ * distances of the listed pairs, out[1] by the one-pass full-precision kernel
+ * (list overflow, or the shortlist switched off with the environment variable
+ * IVF_GP_EXACT_ASSIGN=1, which exists for measurements).  Host call.
+ */
+void ivf_assign_stats(int64_t *out);
 
 /*
  * Index-time encoding of n points x [n][D] (Section 3.2): region = nearest

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     ivf_search_budget,
     ivf_num_kept,
     ivf_coarse_topk,
+    ivf_assign_stats,
     ivf_encode,
     ivf_rotate,
     ivf_kmeans,

@@ -56,6 +56,8 @@ def load_library():
     lib.ivf_num_kept.argtypes = [i32, i32, f32]
     lib.ivf_num_kept.restype = i64
     lib.ivf_coarse_topk.argtypes = [vp, i64, i32, vp, i64, i32, vp, vp, vp]
+    lib.ivf_assign_stats.argtypes = [C.POINTER(C.c_int64)]
+    lib.ivf_assign_stats.restype = None
     lib.ivf_encode.argtypes = [C.POINTER(_Desc), vp, i64, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.ivf_rotate.argtypes = [vp, i64, i32, vp, vp, vp]
     lib.ivf_kmeans.argtypes = [vp, i64, i32, i64, i32, vp, vp, vp, vp]
@@ -248,6 +250,13 @@ def ivf_search_budget(index: IndexHandle, queries: torch.Tensor, nprobe: int, pr
         index.ptr, _ptr(queries), nq, nprobe, prune_frac, max_candidates, k, _ptr(out["ids"]), _ptr(out["dists"]),
         _ptr(out["kept_sub"]), _ptr(out["visited"]), _ptr(out["n_scanned"]), _stream()))
     return out
+
+
+def ivf_assign_stats():
+    """(chunks decided by the shortlist, chunks decided by the one-pass exact kernel) so far in this process."""
+    out = (C.c_int64 * 2)()
+    load_library().ivf_assign_stats(out)
+    return int(out[0]), int(out[1])
 
 
 def ivf_coarse_topk(centroids: torch.Tensor, x: torch.Tensor, P: int):

@@ -136,6 +136,12 @@ __device__ __forceinline__ floatx16 mfma3(const gu32x4 (&bfrag)[2], const gu32x4
 // centroid (row) wc + 32j + 8*(v/4) + 4*(l/32) + v%4, i.e. four groups of four
 // consecutive centroids, which the epilogues store as 128-bit words and reduce
 // without leaving the lane.  buf0 and buf1 each hold (128 + 128) rows x 64 bytes.
+//
+// HI = true: the operands are the hi-only tables of pack_hi_kernel (a row stage of 64 bytes holds 32
+// dimensions: for lane half h the chunks 2h and 2h+1 are its 8 dimensions of the stage's first and
+// second 16), Dp is that table's row length in 4-byte units, and a stage is two products hi*hi: a
+// third of the MFMA work and half the bytes for an approximation of <q,c> whose error the caller bounds.
+template <bool HI = false>
 __device__ __forceinline__ void gemm_tile(const _Float16 *__restrict__ Qp, int64_t nq, int64_t q0,
                                           const _Float16 *__restrict__ Cp, int64_t K, int64_t c0, int Dp,
                                           float *buf0, float *buf1, floatx16 (&acc)[2][2])
@@ -181,28 +187,41 @@ __device__ __forceinline__ void gemm_tile(const _Float16 *__restrict__ Qp, int64
         }
         // the four accumulators are independent: cycle through them so that no MFMA
         // waits for the one issued just before it
+        if (HI) {
 #pragma unroll
-        for (int e = 0; e < 3; ++e)
+            for (int p = 0; p < 2; ++p)
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = mfma3(b[j], a[i], acc[i][j], e);
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, b[j][p]),
+                                                                           __builtin_bit_cast(halfx8, a[i][p]), acc[i][j], 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 3; ++e)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) acc[i][j] = mfma3(b[j], a[i], acc[i][j], e);
+        }
     };
     // The two buffers are separate LDS objects and every step names them statically (the loop
     // is unrolled by two): the compiler can then tell that the operand reads of one buffer do
     // not depend on the copy in flight into the other, and leaves that copy running under the
     // MFMA block.
-    const int stages = Dp / DK;
+    const int stages = Dp / DK;               // (even for the hi/lo tables, any number for the hi-only ones)
     issue(0, buf0);
     for (int s = 0; s < stages; s += 2) {
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's copies of stage s have landed
         __syncthreads();                      // ... and everyone's; all waves are done with the other buffer
-        issue((s + 1) * DK, buf1);            // the number of stages is even
+        if (s + 1 < stages) issue((s + 1) * DK, buf1);
         compute(buf0);
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
-        if (s + 2 < stages) issue((s + 2) * DK, buf0);
-        compute(buf1);
+        if (s + 1 < stages) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            if (s + 2 < stages) issue((s + 2) * DK, buf0);
+            compute(buf1);
+        }
     }
     __syncthreads();   // operands are dead: the buffers may be reused
 }
@@ -770,6 +789,156 @@ __global__ __launch_bounds__(256) void argmin_unpack_kernel(const unsigned long 
     unsigned long long k = best[i];
     out_id[i] = (int32_t)(uint32_t)k;
     if (out_d) out_d[i] = key_float((uint32_t)(k >> 32));
+}
+
+// ---- Nearest centroid through a certified shortlist ----
+// The hi halves alone give <q,c> to about 2^-10 of |q||c| at a third of the MFMA work.  With
+//   approx(q,c) = |q|^2 + |c|^2 - 2 <hi(q), hi(c)>  (fp32 accumulation),
+//   eps(q,c)    = 2^-9 (|q|^2 + |c|^2) + abs_term,
+// the exact squared distance d lies in [approx - eps, approx + eps]: an element of hi(x) differs from x
+// by at most 2^-11 |x_i| (fp16 rounding; below the normal range by at most 2^-39 of the largest
+// magnitude under the row's or table's scale, which abs_term covers), so the inner product is off by at
+// most (2^-10 + 2^-22) sum |q_i c_i| <= (2^-11 + 2^-23)(|q|^2 + |c|^2), the distance by twice that,
+// and the factor 2^-9 leaves as much again for the fp32 roundings of the accumulation and the epilogue.
+// U[q], the smallest approx + eps seen so far, never drops below the true minimum distance of q, so
+// every centroid that attains that minimum has approx - eps <= U[q] whenever it is looked at: the
+// kernel appends each (q, c) with approx - eps <= U[q] to a candidate list, and rerank_kernel decides
+// among the candidates with exact arithmetic.  Stale reads of U only lengthen the list.
+
+// Row r of the hi-only table from row r of the hi/lo table (split_rows_kernel; Dp dimensions, a multiple
+// of 32): per 32 dimensions the 16-byte chunks [k 0-7 | k 16-23 | k 8-15 | k 24-31], so that lane half h
+// of gemm_tile<true> finds its dimensions of the two 16-wide products in chunks 2h and 2h+1.
+__global__ __launch_bounds__(256) void pack_hi_kernel(const _Float16 *__restrict__ P, int64_t n_rows, int Dp,
+                                                      _Float16 *__restrict__ H)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;   // one 16-byte chunk of the output each
+    const int chunks = Dp / 8;
+    if (i >= n_rows * chunks) return;
+    const int64_t r = i / chunks;
+    const int ch = (int)(i % chunks), t = ch >> 2, slot = ch & 3;
+    const int k8 = (slot & 1) * 2 + (slot >> 1);               // which 8 dimensions of the 32: slots 0,1,2,3 -> 0,2,1,3
+    const int dim = 32 * t + 8 * k8;                            // first dimension of the chunk
+    // in the hi/lo table dimension d sits at stage d / 16: [hi k0..7 | lo k0..7 | hi k8..15 | lo k8..15]
+    const _Float16 *src = P + r * (int64_t)Dp * 2 + (dim >> 4) * 32 + ((dim >> 3) & 1) * 16;
+    *reinterpret_cast<gu32x4 *>(H + r * (int64_t)Dp + ch * 8) = *reinterpret_cast<const gu32x4 *>(src);
+}
+
+constexpr float SHORTLIST_KAPPA = 0x1p-9f;
+constexpr int SHORTLIST_SEGS = 64;
+
+// gmax_bits: the centroid table's largest magnitude (bit pattern), D: the dimension; abs_term =
+// 2^-30 (|q|^2 + D gmax^2) covers what lies below fp16's normal range under the table-wide scale.
+// U must be pre-filled with all ones, the segment counters with 0; pairs beyond a segment's capacity are
+// dropped (the caller compares the counters with seg_cap and falls back to the exact kernel).
+__global__ __launch_bounds__(256) void coarse_shortlist_kernel(
+    const _Float16 *__restrict__ Qh, const float *__restrict__ qn, const float *__restrict__ qsi, int64_t nq,
+    const _Float16 *__restrict__ Ch, const float *__restrict__ cn, const float *__restrict__ csi, int64_t K,
+    int Dph, int D, uint32_t *__restrict__ U, int2 *__restrict__ cand_all, unsigned long long *__restrict__ cand_count_all,
+    unsigned long long seg_cap, int tiles_q)
+{
+    // the list is kept in SHORTLIST_SEGS segments with a counter each (128 bytes apart), so that the appends
+    // of different workgroups do not all queue at one address
+    int2 *cand = cand_all + (blockIdx.x % SHORTLIST_SEGS) * seg_cap;
+    unsigned long long *cand_count = cand_count_all + (blockIdx.x % SHORTLIST_SEGS) * 16;
+    const unsigned long long cand_cap = seg_cap;
+    __shared__ __attribute__((aligned(16))) float ops0[DBUF];
+    __shared__ __attribute__((aligned(16))) float ops1[DBUF];
+    __shared__ __attribute__((aligned(16))) float cns[GT];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int64_t q0, c0;
+    if (!tile_of_block(blockIdx.x, tiles_q, q0, c0)) return;
+    const int wq = (wave >> 1) * 64, wc = (wave & 1) * 64;
+    const int l32 = lane & 31, h = lane >> 5;
+    if (threadIdx.x < GT) cns[threadIdx.x] = c0 + threadIdx.x < K ? cn[c0 + threadIdx.x] : 0.f;
+    // the bounds as they stand now, requested before the product so that their latency is hidden under it
+    // (an older bound is a weaker one, never a wrong one)
+    uint32_t seen[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int64_t q = q0 + wq + i * 32 + l32;
+        seen[i] = q < nq ? __hip_atomic_load(&U[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+    }
+    floatx16 acc[2][2];
+    gemm_tile<true>(Qh, nq, q0, Ch, K, c0, Dph, ops0, ops1, acc);
+    const float m2c = -2.f * csi[0];
+    const float gmax = __uint_as_float(reinterpret_cast<const uint32_t *>(csi)[1]);
+    const float abs_c = 0x1p-30f * (float)D * gmax * gmax;
+    const bool whole = c0 + GT <= K;                     // no centroid of the tile lies past the end
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int64_t q = q0 + wq + i * 32 + l32;
+        const bool qok = q < nq;
+        const float qr = qok ? qn[q] : 0.f;
+        const float m2 = qok ? m2c * qsi[q] : 0.f;
+        const float abs_term = fmaf(0x1p-30f, qr, abs_c);
+        // t[j][g] = |q|^2 + |c|^2 of the lane's four consecutive centroids 32 j + 8 g + 4 h ..
+        float4 t[2][4];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 cv = *reinterpret_cast<const float4 *>(&cns[wc + j * 32 + 8 * g + 4 * h]);
+                t[j][g] = make_float4(qr + cv.x, qr + cv.y, qr + cv.z, qr + cv.w);
+            }
+        // upper ends first: this block's smallest approx + eps joins the bound before anything is kept
+        float umin = INFINITY;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float tv[4] = {t[j][g].x, t[j][g].y, t[j][g].z, t[j][g].w};
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float up = fmaf(m2, acc[i][j][4 * g + r], fmaf(SHORTLIST_KAPPA, tv[r], tv[r]));
+                    if (whole || c0 + wc + j * 32 + 8 * g + 4 * h + r < K) umin = fminf(umin, up);
+                }
+            }
+        umin = fmaxf(umin + abs_term, 0.f);
+        umin = fminf(umin, __shfl_xor(umin, 32, WAVE));
+        if (!qok) continue;
+        float bound = umin;
+        if (seen[i] != ~0u) bound = fminf(bound, __uint_as_float(seen[i]));
+        // (non-negative floats order like their bit patterns)
+        if (h == 0 && __float_as_uint(umin) < seen[i]) atomicMin(&U[q], __float_as_uint(umin));
+        bound += abs_term;   // lo = approx - eps <= bound  <=>  approx - kappa t <= bound + abs_term
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float tv[4] = {t[j][g].x, t[j][g].y, t[j][g].z, t[j][g].w};
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float lo = fmaf(m2, acc[i][j][4 * g + r], fmaf(-SHORTLIST_KAPPA, tv[r], tv[r]));
+                    const int cl = wc + j * 32 + 8 * g + 4 * h + r;
+                    if (lo <= bound && (whole || c0 + cl < K)) {
+                        const unsigned long long at = atomicAdd(cand_count, 1ull);
+                        if (at < cand_cap) cand[at] = make_int2((int)q, (int)(c0 + cl));
+                    }
+                }
+            }
+    }
+}
+
+// Exact decision among the candidates: one wavefront per pair computes |x - c|^2 from the fp32 rows
+// (differences squared, summed in a tree over the lanes: a few ulps) and merges (distance, id) into
+// best[q] with a 64-bit atomic minimum.  best must be pre-filled with all ones.
+// Grid: (quarter of the longest segment, SHORTLIST_SEGS).
+__global__ __launch_bounds__(256) void rerank_kernel(const float *__restrict__ X, const float *__restrict__ C, int D,
+                                                     const int2 *__restrict__ cand_all, const unsigned long long *__restrict__ cand_count_all,
+                                                     unsigned long long seg_cap, unsigned long long *__restrict__ best)
+{
+    const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if ((unsigned long long)i >= cand_count_all[blockIdx.y * 16]) return;
+    const int2 qc = cand_all[blockIdx.y * seg_cap + i];
+    const float *x = X + (int64_t)qc.x * D, *c = C + (int64_t)qc.y * D;
+    float s = 0.f;
+    for (int k = lane; k < D; k += WAVE) {
+        const float u = x[k] - c[k];
+        s = fmaf(u, u, s);
+    }
+    s = wave_sum(s);
+    if (lane == 0) atomicMin(&best[qc.x], ((unsigned long long)float_key(s) << 32) | (uint32_t)qc.y);
 }
 
 // The P closest centroids of each query row of Dt by (distance, id), written

@@ -2,9 +2,11 @@
 // management and the launch sequence of the query path.  gfx950 only.
 #include "../../include/ivf_gp.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -706,20 +708,33 @@ extern "C" int ivf_search(ivf_index *ix, const float *queries, int64_t nq, int n
 
 namespace {
 
+std::atomic<int64_t> g_assign_short{0}, g_assign_exact{0};
+
 // Nearest-centroid assignment (P = 1) with buffers that live across calls: the packed centroid
 // table and the per-chunk query scratch.  No distance tile: the minimum is fused into the GEMM.
+//
+// Two passes: the hi halves of the operands alone (a third of the MFMA work) give every row a short
+// list of centroids that may be its nearest, with a proven error bound (coarse_shortlist_kernel), and
+// the exact distances of the listed pairs decide (rerank_kernel).  A chunk whose list overflows (rows
+// with very many centroids at nearly the same distance) is redone by the exact kernel.
 struct ArgminCtx {
     int64_t K = 0, chunk = 0;
     int D = 0, Dp = 0;
     float *cn = nullptr, *csi = nullptr, *xn = nullptr, *xsi = nullptr;
-    _Float16 *cpk = nullptr, *xpk = nullptr;
-    unsigned long long *best = nullptr;
+    _Float16 *cpk = nullptr, *xpk = nullptr, *chk = nullptr, *xhk = nullptr;   // hi/lo tables, hi-only tables
+    unsigned long long *best = nullptr, *cand_count = nullptr;
+    uint32_t *U = nullptr;
+    int2 *cand = nullptr;
+    unsigned long long seg_cap = 0;
+    const float *centroids = nullptr;          // the caller's table, as of the last set_centroids
+    bool shortlist = true;
+    int64_t chunks_short = 0, chunks_exact = 0;   // how the chunks of all run() calls were decided
     ArgminCtx() = default;
     ArgminCtx(const ArgminCtx &) = delete;
     ArgminCtx &operator=(const ArgminCtx &) = delete;
     ~ArgminCtx()
     {
-        void *owned[] = {cn, csi, xn, xsi, cpk, xpk, best};
+        void *owned[] = {cn, csi, xn, xsi, cpk, xpk, chk, xhk, best, cand_count, U, cand};
         for (void *p : owned)
             if (p) (void)hipFree(p);
     }
@@ -740,11 +755,73 @@ struct ArgminCtx {
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&xsi), (size_t)chunk * sizeof(float)));
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&xpk), (size_t)packed_rows(chunk) * Dp * 2 * sizeof(_Float16)));
         HIPCHK(hipMalloc(reinterpret_cast<void **>(&best), (size_t)chunk * sizeof(unsigned long long)));
+        const char *off = getenv("IVF_GP_EXACT_ASSIGN");   // (for measurements: the one-pass exact kernel only)
+        shortlist = !(off && off[0] == '1');
+        if (shortlist) {
+            // room for 32 listed centroids per row on average, at least 2^16 pairs per segment
+            seg_cap = (unsigned long long)(32 * chunk + SHORTLIST_SEGS - 1) / SHORTLIST_SEGS;
+            if (seg_cap < (1ull << 16)) seg_cap = 1ull << 16;
+            HIPCHK(hipMalloc(reinterpret_cast<void **>(&chk), (size_t)packed_rows(K) * Dp * sizeof(_Float16)));
+            HIPCHK(hipMalloc(reinterpret_cast<void **>(&xhk), (size_t)packed_rows(chunk) * Dp * sizeof(_Float16)));
+            HIPCHK(hipMalloc(reinterpret_cast<void **>(&U), (size_t)(chunk + 2) * sizeof(uint32_t)));   // filled in 64-bit words
+            HIPCHK(hipMalloc(reinterpret_cast<void **>(&cand), (size_t)seg_cap * SHORTLIST_SEGS * sizeof(int2)));
+            HIPCHK(hipMalloc(reinterpret_cast<void **>(&cand_count), (size_t)SHORTLIST_SEGS * 16 * sizeof(unsigned long long)));
+        }
         return IVF_OK;
     }
-    int set_centroids(const float *centroids, hipStream_t st)
+    int set_centroids(const float *centroids_, hipStream_t st)
     {
-        return pack_rows(centroids, K, D, reinterpret_cast<uint32_t *>(csi + 1), cpk, cn, csi, st);
+        centroids = centroids_;
+        int rc = pack_rows(centroids, K, D, reinterpret_cast<uint32_t *>(csi + 1), cpk, cn, csi, st);
+        if (rc || !shortlist) return rc;
+        const int64_t chunks16 = K * (Dp / 8);
+        pack_hi_kernel<<<dim3((unsigned)((chunks16 + 255) / 256)), dim3(256), 0, st>>>(cpk, K, Dp, chk);
+        LAUNCHCHK("pack_hi_kernel");
+        return IVF_OK;
+    }
+    // the exact one-pass kernel on the packed chunk
+    int run_exact(int64_t m, hipStream_t st)
+    {
+        const int tiles_q = (int)((m + GT - 1) / GT);
+        const int64_t grid = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * ((K + GT - 1) / GT);
+        if (grid >= (1ll << 24)) return fail(IVF_EINVAL, "coarse tile grid too large");
+        fill_u64_kernel<<<dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st>>>(best, m, ~0ull);
+        LAUNCHCHK("fill_u64_kernel");
+        coarse_argmin_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xpk, xn, xsi, m, cpk, cn, csi, K, Dp, best, tiles_q);
+        LAUNCHCHK("coarse_argmin_kernel");
+        ++chunks_exact; ++g_assign_exact;
+        return IVF_OK;
+    }
+    // shortlist + exact decision; *overflow = the list did not hold every candidate (best[] is then incomplete)
+    int run_shortlist(const float *x, int64_t m, bool *overflow, hipStream_t st)
+    {
+        const int tiles_q = (int)((m + GT - 1) / GT);
+        const int64_t grid = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * ((K + GT - 1) / GT);
+        if (grid >= (1ll << 24)) return fail(IVF_EINVAL, "coarse tile grid too large");
+        const int64_t chunks16 = m * (Dp / 8);
+        pack_hi_kernel<<<dim3((unsigned)((chunks16 + 255) / 256)), dim3(256), 0, st>>>(xpk, m, Dp, xhk);
+        LAUNCHCHK("pack_hi_kernel");
+        fill_u64_kernel<<<dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st>>>(best, m, ~0ull);
+        LAUNCHCHK("fill_u64_kernel");
+        // U: 32-bit words, two per 64-bit fill; the counters likewise
+        fill_u64_kernel<<<dim3((unsigned)(((m + 1) / 2 + 255) / 256)), dim3(256), 0, st>>>(reinterpret_cast<unsigned long long *>(U), (m + 1) / 2, ~0ull);
+        LAUNCHCHK("fill_u64_kernel");
+        fill_u64_kernel<<<dim3((SHORTLIST_SEGS * 16 + 255) / 256), dim3(256), 0, st>>>(cand_count, SHORTLIST_SEGS * 16, 0ull);
+        LAUNCHCHK("fill_u64_kernel");
+        coarse_shortlist_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xhk, xn, xsi, m, chk, cn, csi, K, Dp / 2, D, U, cand,
+                                                                            cand_count, seg_cap, tiles_q);
+        LAUNCHCHK("coarse_shortlist_kernel");
+        unsigned long long counts[SHORTLIST_SEGS * 16];
+        HIPCHK(hipMemcpyAsync(counts, cand_count, sizeof(counts), hipMemcpyDeviceToHost, st));
+        HIPCHK(hipStreamSynchronize(st));
+        unsigned long long longest = 0;
+        for (int sgm = 0; sgm < SHORTLIST_SEGS; ++sgm) longest = counts[sgm * 16] > longest ? counts[sgm * 16] : longest;
+        *overflow = longest > seg_cap || longest == 0;
+        if (*overflow) return IVF_OK;
+        rerank_kernel<<<dim3((unsigned)((longest + 3) / 4), SHORTLIST_SEGS), dim3(256), 0, st>>>(x, centroids, D, cand, cand_count, seg_cap, best);
+        LAUNCHCHK("rerank_kernel");
+        ++chunks_short; ++g_assign_short;
+        return IVF_OK;
     }
     // out_id[i] = nearest centroid of x[i] by (distance, id), out_d[i] (may be NULL) its squared distance
     int run(const float *x, int64_t n, int32_t *out_id, float *out_d, hipStream_t st)
@@ -752,14 +829,10 @@ struct ArgminCtx {
         int rc;
         for (int64_t q0 = 0; q0 < n; q0 += chunk) {
             const int64_t m = (n - q0 < chunk) ? n - q0 : chunk;
-            fill_u64_kernel<<<dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st>>>(best, m, ~0ull);
-            LAUNCHCHK("fill_u64_kernel");
             if ((rc = pack_rows(x + q0 * D, m, D, nullptr, xpk, xn, xsi, st))) return rc;
-            const int tiles_q = (int)((m + GT - 1) / GT);
-            const int64_t grid = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * ((K + GT - 1) / GT);
-            if (grid >= (1ll << 24)) return fail(IVF_EINVAL, "coarse tile grid too large");
-            coarse_argmin_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xpk, xn, xsi, m, cpk, cn, csi, K, Dp, best, tiles_q);
-            LAUNCHCHK("coarse_argmin_kernel");
+            bool overflow = true;
+            if (shortlist && (rc = run_shortlist(x + q0 * D, m, &overflow, st))) return rc;
+            if (overflow && (rc = run_exact(m, st))) return rc;
             argmin_unpack_kernel<<<dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st>>>(best, m, out_id + q0, out_d ? out_d + q0 : nullptr);
             LAUNCHCHK("argmin_unpack_kernel");
         }
@@ -818,6 +891,12 @@ int coarse_topk_tiled(const float *centroids, int64_t K, int D, const float *x, 
 }
 
 }  // namespace
+
+extern "C" void ivf_assign_stats(int64_t *out)
+{
+    out[0] = g_assign_short.load();
+    out[1] = g_assign_exact.load();
+}
 
 extern "C" int ivf_coarse_topk(const float *centroids, int64_t K, int D, const float *x, int64_t nq, int P,
                                int32_t *out_id, float *out_d, void *hip_stream)
