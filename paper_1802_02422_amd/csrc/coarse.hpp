@@ -919,6 +919,198 @@ __global__ __launch_bounds__(256) void coarse_shortlist_kernel(
     }
 }
 
+// The same pass with the structure of the sweep kernel, for SH = 3 or 4 hi-only stages (packed dimension
+// 96 or 128): a workgroup keeps the hi fragments of ONE query tile in registers and sweeps `tiles_per_wg`
+// consecutive centroid tiles through two LDS buffers of a whole tile each, one workgroup barrier per tile
+// (the copies of tile t + 1 are issued right behind the barrier of tile t and waited for at the barrier of
+// tile t + 1).  The running minimum of approx + eps over the sweep stays in registers and reaches U[q]
+// once, at the end.
+// Only direct-to-LDS copies write `ring` and `cns`, only explicit ds_read instructions read them.
+template <int SH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SH == 3 ? 3 : 2, SH == 3 ? 3 : 2))) void coarse_shortlist_sweep_kernel(
+    const _Float16 *__restrict__ Qh, const float *__restrict__ qn, const float *__restrict__ qsi, int64_t nq,
+    const _Float16 *__restrict__ Ch, const float *__restrict__ cn, const float *__restrict__ csi, int64_t K,
+    int D, uint32_t *__restrict__ U, int2 *__restrict__ cand_all, unsigned long long *__restrict__ cand_count_all,
+    unsigned long long seg_cap, int tiles_q, int tiles_c, int tiles_per_wg)
+{
+    typedef const __attribute__((address_space(1))) void *gptr_t;
+    typedef __attribute__((address_space(3))) void *lptr_t;
+    constexpr int Dpf = SH * DK;                           // floats per row of the hi-only tables
+    constexpr int SLOT = GT * ROWF;
+    __shared__ __attribute__((aligned(16))) float ring[2][SH * SLOT];
+    __shared__ __attribute__((aligned(16))) float cns[2][GT];
+    int2 *cand = cand_all + (blockIdx.x % SHORTLIST_SEGS) * seg_cap;
+    unsigned long long *cand_count = cand_count_all + (blockIdx.x % SHORTLIST_SEGS) * 16;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, h = lane >> 5;
+    const int wq = (wave >> 1) * 64, wc = (wave & 1) * 64;
+    const int tq_per = (tiles_q + N_XCD - 1) / N_XCD;
+    const int xcd = (int)(blockIdx.x % N_XCD);
+    const int64_t local = blockIdx.x / N_XCD;
+    const int tq = (int)(local % tq_per) * N_XCD + xcd;
+    if (tq >= tiles_q) return;
+    const int tb = (int)(local / tq_per) * tiles_per_wg;
+    int t_end = tb < tiles_c ? tiles_c - tb : 0;
+    if (t_end > tiles_per_wg) t_end = tiles_per_wg;
+    if (t_end <= 0) return;
+    const int64_t q0 = (int64_t)tq * GT;
+
+    // this wavefront's copies of a tile: rows 32 wave + 16 n + lane / 4 (n = 0, 1) of each stage, and
+    // (wavefronts 0, 1) 64 of the tile's norms (index clamped at the end of the table: never used there)
+    const int rl = wave * 32 + (lane >> 2);
+    const int fl = (lane & 3) ^ ((lane >> 4) & 3);
+    const float *cbase = reinterpret_cast<const float *>(Ch) + (int64_t)rl * Dpf + fl * 4;
+    auto issue_tile = [&](int t) {
+        const int tc = t < t_end ? t : t_end - 1;            // past the range: the last tile again, never read
+        if (wave < 2) {
+            const int64_t cnx = (int64_t)(tb + tc) * GT + wave * 64 + lane;
+            __builtin_amdgcn_global_load_lds((gptr_t)(cn + (cnx < K ? cnx : K - 1)), (lptr_t)(&cns[t & 1][wave * 64]), 4, 0, 0);
+        }
+        const float *src = cbase + (int64_t)(tb + tc) * GT * Dpf;
+        float *dst = &ring[t & 1][wave * 512];
+        // (one instruction in a rolled loop: the compiler tracks only a handful of distinct LDS copies exactly)
+#pragma nounroll
+        for (int n = 0; n < 2 * SH; ++n)
+            __builtin_amdgcn_global_load_lds((gptr_t)(src + (n >> 1) * DK + (int64_t)(n & 1) * 16 * Dpf),
+                                             (lptr_t)(dst + (n >> 1) * SLOT + (n & 1) * 256), 16, 0, 0);
+    };
+    issue_tile(0);
+
+    gu32x4 afr[SH][2][2];
+    float qr[2], m2[2], abs_term[2], lmin[2];
+    uint32_t seen[2];
+    bool qok[2];
+    {
+        const float m2c = -2.f * csi[0];
+        const float gmax = __uint_as_float(reinterpret_cast<const uint32_t *>(csi)[1]);
+        const float abs_c = 0x1p-30f * (float)D * gmax * gmax;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int64_t q = q0 + wq + i * 32 + l32;
+            qok[i] = q < nq;
+            const gu32x4 *row = reinterpret_cast<const gu32x4 *>(reinterpret_cast<const float *>(Qh) + q * Dpf) + 2 * h;
+#pragma unroll
+            for (int s = 0; s < SH; ++s) {
+                afr[s][i][0] = row[s * 4 + 0];
+                afr[s][i][1] = row[s * 4 + 1];
+            }
+            qr[i] = qok[i] ? qn[q] : 0.f;
+            m2[i] = qok[i] ? m2c * qsi[q] : 0.f;
+            abs_term[i] = fmaf(0x1p-30f, qr[i], abs_c);
+            // the bound as it stands now (an older bound is a weaker one, never a wrong one)
+            seen[i] = qok[i] ? __hip_atomic_load(&U[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+            lmin[i] = INFINITY;
+        }
+    }
+
+    for (int t = 0; t < t_end; ++t) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // this wavefront's copies of tile t (issued a tile ago) are in
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // ... and everyone's; tile t - 1's buffer is free
+        issue_tile(t + 1);
+        const int64_t c0 = (int64_t)(tb + t) * GT;
+        const bool whole = c0 + GT <= K;
+        // One half of the wavefront's 64 centroids at a time, both blocks of 32 queries: two accumulators live
+        // instead of four, every centroid fragment still read from LDS once.  Registers are what limits the
+        // wavefronts per SIMD here, and three of them hide the LDS and barrier latencies that two leave open.
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            floatx16 acc[2];
+            const int rb = wc + j * 32 + l32;
+#pragma unroll
+            for (int s = 0; s < SH; ++s) {
+                gu32x4 b[2];
+                const uint32_t bs = (uint32_t)reinterpret_cast<uintptr_t>(&ring[t & 1][s * SLOT]);
+#pragma unroll
+                for (int p = 0; p < 2; ++p) {
+                    const uint32_t at = bs + 4u * (uint32_t)(rb * ROWF + (((2 * h + p) ^ ((rb >> 2) & 3)) << 2));
+                    asm volatile("ds_read_b128 %0, %1" : "=v"(b[p]) : "v"(at));
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(b[0]), "+v"(b[1]));
+#pragma unroll
+                for (int p = 0; p < 2; ++p)
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        floatx16 c_in = acc[i];
+                        if (s == 0 && p == 0) {
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) c_in[v] = 0.f;
+                        }
+                        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, b[p]),
+                                                                        __builtin_bit_cast(halfx8, afr[s][i][p]), c_in, 0, 0, 0);
+                    }
+            }
+            // the norms of the lane's 16 centroids of this half (copied to LDS behind the compiler's back:
+            // explicit reads and wait)
+            floatx4 cv[4];
+            {
+                const uint32_t cb = (uint32_t)reinterpret_cast<uintptr_t>(&cns[t & 1][wc + j * 32 + 4 * h]);
+#pragma unroll
+                for (int g = 0; g < 4; ++g) asm volatile("ds_read_b128 %0, %1" : "=v"(cv[g]) : "v"(cb + 32u * (uint32_t)g));
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(cv[0]), "+v"(cv[1]), "+v"(cv[2]), "+v"(cv[3]));
+            }
+            uint32_t valid = 0xFFFFu;                          // bit v: the lane's centroid v lies inside the table
+            if (!whole) {
+                valid = 0;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) valid |= (c0 + wc + j * 32 + 8 * (v >> 2) + 4 * h + (v & 3) < K ? 1u : 0u) << v;
+            }
+            const float cmax = fmaxf(fmaxf(fmaxf(fmaxf(cv[0][0], cv[0][1]), fmaxf(cv[0][2], cv[0][3])), fmaxf(fmaxf(cv[1][0], cv[1][1]), fmaxf(cv[1][2], cv[1][3]))),
+                                     fmaxf(fmaxf(fmaxf(cv[2][0], cv[2][1]), fmaxf(cv[2][2], cv[2][3])), fmaxf(fmaxf(cv[3][0], cv[3][1]), fmaxf(cv[3][2], cv[3][3]))));
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                // a = approx, in place, and its minimum over the lane's centroids: with their largest
+                // t = |q|^2 + |c|^2, three operations per distance decide, nearly always, that the lane has
+                // nothing to report
+                float amin = INFINITY;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float a = fmaf(m2[i], acc[i][v], qr[i] + cv[v >> 2][v & 3]);
+                    acc[i][v] = a;
+                    if (whole || (valid >> v & 1)) amin = fminf(amin, a);
+                }
+                float bound = lmin[i];
+                if (seen[i] != ~0u) bound = fminf(bound, __uint_as_float(seen[i]));
+                // every lower end of the lane is at least amin - kappa tmax - abs_term, every upper end at least
+                // amin: above the bound, the lane can neither list a centroid nor lower the bound
+                const bool look = fmaf(-SHORTLIST_KAPPA, qr[i] + cmax, amin) - abs_term[i] <= bound;
+                if (__any(look)) {
+                    // the smallest upper end a + kappa t + abs_term of the query in this half, exactly
+                    float umin = INFINITY;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float up = fmaf(SHORTLIST_KAPPA, qr[i] + cv[v >> 2][v & 3], acc[i][v]);
+                        if (whole || (valid >> v & 1)) umin = fminf(umin, up);
+                    }
+                    umin = fmaxf(umin + abs_term[i], 0.f);
+                    umin = fminf(umin, __shfl_xor(umin, 32, WAVE));   // the other lane half holds the other 16 centroids
+                    lmin[i] = fminf(lmin[i], umin);
+                    bound = fminf(bound, lmin[i]) + abs_term[i];   // approx - eps <= bound  <=>  a - kappa t <= bound + abs_term
+                    uint32_t todo = 0;                                // which of the lane's distances pass
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        todo |= (fmaf(-SHORTLIST_KAPPA, qr[i] + cv[v >> 2][v & 3], acc[i][v]) <= bound ? 1u : 0u) << v;
+                    todo &= valid;
+                    if (!qok[i]) todo = 0;
+                    while (todo) {
+                        const int v = __builtin_ctz(todo);
+                        todo &= todo - 1;
+                        const unsigned long long at = atomicAdd(cand_count, 1ull);
+                        if (at < seg_cap)
+                            cand[at] = make_int2((int)(q0 + wq + i * 32 + l32), (int)(c0 + wc + j * 32 + 8 * (v >> 2) + 4 * h + (v & 3)));
+                    }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);   // the next half's products start with this half's registers free
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // no copy into LDS may outlive the workgroup
+#pragma unroll
+    for (int i = 0; i < 2; ++i)   // (non-negative floats order like their bit patterns)
+        if (qok[i] && h == 0 && __float_as_uint(lmin[i]) < seen[i]) atomicMin(&U[q0 + wq + i * 32 + l32], __float_as_uint(lmin[i]));
+}
+
 // Exact decision among the candidates: one wavefront per pair computes |x - c|^2 from the fp32 rows
 // (differences squared, summed in a tree over the lanes: a few ulps) and merges (distance, id) into
 // best[q] with a 64-bit atomic minimum.  best must be pre-filled with all ones.

@@ -808,9 +808,22 @@ struct ArgminCtx {
         LAUNCHCHK("fill_u64_kernel");
         fill_u64_kernel<<<dim3((SHORTLIST_SEGS * 16 + 255) / 256), dim3(256), 0, st>>>(cand_count, SHORTLIST_SEGS * 16, 0ull);
         LAUNCHCHK("fill_u64_kernel");
-        coarse_shortlist_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xhk, xn, xsi, m, chk, cn, csi, K, Dp / 2, D, U, cand,
-                                                                            cand_count, seg_cap, tiles_q);
-        LAUNCHCHK("coarse_shortlist_kernel");
+        if (Dp == 96 || Dp == 128) {   // query tile in registers, centroid tiles swept
+            const int per_wg = 64;
+            const int64_t tiles_c = (K + GT - 1) / GT;
+            const int64_t g2 = (int64_t)((tiles_q + N_XCD - 1) / N_XCD) * N_XCD * ((tiles_c + per_wg - 1) / per_wg);
+            if (Dp == 96)
+                coarse_shortlist_sweep_kernel<3><<<dim3((unsigned)g2), dim3(256), 0, st>>>(xhk, xn, xsi, m, chk, cn, csi, K, D, U, cand, cand_count,
+                                                                                         seg_cap, tiles_q, (int)tiles_c, per_wg);
+            else
+                coarse_shortlist_sweep_kernel<4><<<dim3((unsigned)g2), dim3(256), 0, st>>>(xhk, xn, xsi, m, chk, cn, csi, K, D, U, cand, cand_count,
+                                                                                         seg_cap, tiles_q, (int)tiles_c, per_wg);
+            LAUNCHCHK("coarse_shortlist_sweep_kernel");
+        } else {
+            coarse_shortlist_kernel<<<dim3((unsigned)grid), dim3(256), 0, st>>>(xhk, xn, xsi, m, chk, cn, csi, K, Dp / 2, D, U, cand,
+                                                                                cand_count, seg_cap, tiles_q);
+            LAUNCHCHK("coarse_shortlist_kernel");
+        }
         unsigned long long counts[SHORTLIST_SEGS * 16];
         HIPCHK(hipMemcpyAsync(counts, cand_count, sizeof(counts), hipMemcpyDeviceToHost, st));
         HIPCHK(hipStreamSynchronize(st));
