@@ -109,7 +109,7 @@ def build(spec: sd.WorkloadSpec, mix: sd.Mixture, mode: str = "kmeans", chunk: i
         rin = lab.int().contiguous() if mode == "mixture" else None
         r, s_, cd, by, _ = B.ivf_encode(desc, X, region_in=rin)
         if c == 0 and mode == "mixture":
-            ns = min(100_000, n)
+            ns = min(1_000_000, n)
             pick = sd.draw_indices(n, ns, "assign-check", dev)
             exact = B.ivf_coarse_topk(cent, X[pick].contiguous(), 1)[0].view(-1)
             stats["label_vs_exact_assignment"] = (exact == r[pick]).float().mean().item()
