@@ -42,8 +42,11 @@ def _check(C, Q, gid, gd):
     return int((~clear).sum())
 
 
-@pytest.mark.parametrize("D,K,nq", [(96, 4096, 3000), (128, 1000, 700), (20, 300, 1), (100, 2500, 129), (64, 64, 50)])
+@pytest.mark.parametrize("D,K,nq", [(96, 4096, 3000), (128, 1000, 700), (20, 300, 1), (100, 2500, 129), (64, 64, 50),
+                                    (96, 1000, 300), (96, 50, 40), (96, 20000, 500), (128, 128, 128)])
 def test_shortlist_assignment_is_the_exact_nearest(D, K, nq):
+    """Widths that take the swept kernel (96, 128, 100 -> 128) and the tile kernel (20, 64); whole and partial
+    last centroid tiles, fewer centroids than a tile, more tiles than one workgroup sweeps, one row."""
     print("case: shortlist", D, K, nq, flush=True)
     rng = np.random.default_rng(7 * D + K + nq)
     # clustered points around the centroids, rows of very different magnitude, a point that is a centroid
