@@ -215,7 +215,13 @@ int64_t ivf_num_kept(int nprobe, int L, float prune_frac);
  * centroids that may be its nearest, and exact fp32 distances of the listed
  * pairs decide, ties to the smaller id; a chunk of rows whose list overflows
  * is redone by the one-pass full-precision kernel.  The result is the exact
- * nearest centroid either way.
+ * nearest centroid either way; the two ways round their distances
+ * differently (differences squared and summed, against norms minus twice the
+ * inner product), so a row whose two nearest centroids are closer to each
+ * other than fp32 rounding resolves may get either of them.  Which way a chunk
+ * goes depends on the data alone as long as its list is far from full, which
+ * is the case unless most rows have dozens of centroids within 2^-8 of their
+ * nearest distance.
  */
 int ivf_coarse_topk(const float *centroids, int64_t K, int D, const float *x, int64_t nq, int P,
                     int32_t *out_id, float *out_d, void *hip_stream);
