@@ -1189,20 +1189,18 @@ __global__ __launch_bounds__(BLOCK) void probe_select_kernel(const float *__rest
 // global-memory path of probe_select_kernel.  Dynamic LDS: 2P + 3 + max(nb, 2 PS_CAP) words.
 constexpr int PS_NB_MAX = 16384, PS_P_MAX = 256, PS_CAP = 4096;
 
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void probe_select_lds_kernel(const float *__restrict__ Dt, int64_t ldt,
-                                                                const float *__restrict__ bm, int64_t K,
-                                                                int nb, int P,
-                                                                int32_t *__restrict__ probe_id,
-                                                                float *__restrict__ probe_d)
+// (the body, for query q of the batch: also the first half of select_score_prune_kernel)
+__device__ __forceinline__ void probe_select_lds_body(const float *__restrict__ Dt, int64_t ldt,
+                                                      const float *__restrict__ bm, int64_t K, int nb, int P,
+                                                      int32_t *__restrict__ probe_id, float *__restrict__ probe_d,
+                                                      int64_t q, int *ps_dyn)
 {
     constexpr int BLOCK = 1024;
     __shared__ SelectShared sh;
     __shared__ uint32_t nflag_s;
-    extern __shared__ __attribute__((aligned(16))) int ps_dyn[];
     int *blist = ps_dyn;                                           // 2P flagged blocks
     uint32_t *keys = reinterpret_cast<uint32_t *>(ps_dyn + ((2 * P + 3) & ~3));   // (16-byte aligned) nb block-minimum keys, then the survivors
     const int tid = threadIdx.x;
-    const int64_t q = blockIdx.x;
     const float *row = Dt + q * ldt;
     const float *bmr = bm + q * nb;
     if ((nb & 3) == 0) {   // rows of bm are then 16-byte aligned: four loads in flight per thread, 128 bits each
@@ -1300,6 +1298,16 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                                         probe_id[q * P + pos] = si[i];
                                         probe_d[q * P + pos] = key_float(k);
                                     });
+}
+
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void probe_select_lds_kernel(const float *__restrict__ Dt, int64_t ldt,
+                                                                const float *__restrict__ bm, int64_t K,
+                                                                int nb, int P,
+                                                                int32_t *__restrict__ probe_id,
+                                                                float *__restrict__ probe_d)
+{
+    extern __shared__ __attribute__((aligned(16))) int ps_dyn[];
+    probe_select_lds_body(Dt, ldt, bm, K, nb, P, probe_id, probe_d, blockIdx.x, ps_dyn);
 }
 
 }  // namespace ivf

@@ -19,6 +19,7 @@
 #include "budget.hpp"
 #include "coarse.hpp"
 #include "encode.hpp"
+#include "latency.hpp"
 #include "layout.hpp"
 #include "query.hpp"
 #include "scan.hpp"
@@ -437,7 +438,7 @@ int check_search_args(const ivf_index *ix, const float *queries, int64_t nq, int
 }
 
 // Dynamic LDS sizes of the stage kernels; raises the kernels' limits where they exceed the default window.
-struct LdsPlan { size_t scan, merge, sp; };
+struct LdsPlan { size_t scan, merge, sp, ssp; };   // ssp: the fused selection + scoring launch of small batches
 
 int plan_lds(const ivf_index *ix, int P, int k, const SearchPlan &pl, LdsPlan &l)
 {
@@ -453,6 +454,16 @@ int plan_lds(const ivf_index *ix, int P, int k, const SearchPlan &pl, LdsPlan &l
                          : PL > 4096 ? reinterpret_cast<const void *>(&score_prune_kernel<1024, 4>)
                                      : reinterpret_cast<const void *>(&score_prune_kernel<256, 4>);
         HIPCHK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l.sp));
+    }
+    {   // the fused launch needs what either half needs (see launch_probe_select for the selection's share)
+        const int64_t nb = (ix->K + BMW - 1) / BMW;
+        const size_t sel = ((size_t)2 * P + 3 + (nb > 2 * PS_CAP ? nb : 2 * PS_CAP)) * sizeof(int);
+        l.ssp = sel > l.sp ? sel : l.sp;
+        if (P <= PS_P_MAX && nb <= PS_NB_MAX && PL > 4096 && l.ssp > 48 * 1024) {
+            const void *fn = PL > 16384 ? reinterpret_cast<const void *>(&select_score_prune_kernel<8>)
+                                        : reinterpret_cast<const void *>(&select_score_prune_kernel<4>);
+            HIPCHK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l.ssp));
+        }
     }
     if (l.merge > 40 * 1024)
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&merge_kernel<256>),
@@ -493,7 +504,10 @@ int run_search(ivf_index *ix, const SearchArgs &a, const SearchPlan &pl, const L
         if ((rc = pack_rows(Q, n, D, nullptr, ws.qpk, ws.qn, ws.qsi, st))) return rc;
         if ((rc = launch_coarse(ws.qpk, ws.qn, ws.qsi, n, ix->cpk, ix->cnorm, ix->csi, K, Dp, ws.dt, ws.bm, st))) return rc;
         if ((rc = mark(1))) return rc;
-        if ((rc = launch_probe_select(ws.dt, ws.bm, n, K, P, pid, pd, st))) return rc;
+        // small batches: the selection runs inside the scoring launch (one workgroup per query does both)
+        const int nb = (int)((K + BMW - 1) / BMW);
+        const bool fused = n <= 2 * SKQ && P <= PS_P_MAX && nb <= PS_NB_MAX && PL > 4096;
+        if (!fused && (rc = launch_probe_select(ws.dt, ws.bm, n, K, P, pid, pd, st))) return rc;
         if ((rc = mark(2))) return rc;
 
         int64_t *ks = a.kept_sub_out ? a.kept_sub_out + q0 * S : nullptr;
@@ -510,10 +524,17 @@ int run_search(ivf_index *ix, const SearchArgs &a, const SearchPlan &pl, const L
     score_prune_kernel<BLK, MV><<<dim3((unsigned)(2 * n)), dim3(BLK), lds.sp, st>>>(                                \
         ws.dt, dt_stride(K), K, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, ws.desc, ks, ns, n, Qt, \
         D, M, ix->codebook, ws.lut)
-        if (PL > 16384) IVF_SP_LAUNCH(1024, 8);
+#define IVF_SSP_LAUNCH(MV)                                                                                          \
+    select_score_prune_kernel<MV><<<dim3((unsigned)(2 * n)), dim3(1024), lds.ssp, st>>>(                             \
+        ws.dt, dt_stride(K), ws.bm, K, nb, pid, pd, P, L, ix->nbr, ix->cst, ix->alpha, S, ix->sub_info, ws.desc, ks, ns, \
+        n, Qt, D, M, ix->codebook, ws.lut)
+        if (fused && PL > 16384) IVF_SSP_LAUNCH(8);
+        else if (fused) IVF_SSP_LAUNCH(4);
+        else if (PL > 16384) IVF_SP_LAUNCH(1024, 8);
         else if (PL > 4096) IVF_SP_LAUNCH(1024, 4);
         else IVF_SP_LAUNCH(256, 4);
 #undef IVF_SP_LAUNCH
+#undef IVF_SSP_LAUNCH
         LAUNCHCHK("score_prune_kernel");
         if (a.budget > 0) {
             const uint32_t R = a.budget > 0xFFFFFFFFll ? 0xFFFFFFFFu : (uint32_t)a.budget;

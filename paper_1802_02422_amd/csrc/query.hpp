@@ -50,30 +50,23 @@ __device__ __forceinline__ void lut_body(const float *__restrict__ Qrow, int D, 
 // table (lut_body, from Qt = the queries, rotated if the index has a rotation) while the first nq
 // gather and select; the two halves share nothing, and the table work hides under the gathers.
 // Dynamic LDS must also hold D floats.
+// (the body of a scoring workgroup, for query q of the batch: also the second half of select_score_prune_kernel)
 template <int BLOCK, int MAXV>
-__global__ __launch_bounds__(BLOCK) void score_prune_kernel(
+__device__ __forceinline__ void score_prune_body(
     const float *__restrict__ Dt, int64_t ldt, int64_t K, const int32_t *__restrict__ probe_id,
     const float *__restrict__ probe_d, int P, int L, const int32_t *__restrict__ nbr,
     const float *__restrict__ cst, const float *__restrict__ alpha, int S,
     const uint4 *__restrict__ sub_info,
     SubDesc *__restrict__ desc, int64_t *__restrict__ kept_sub, int64_t *__restrict__ n_scanned,
-    int64_t nq, const float *__restrict__ Qt, int D, int M, const float *__restrict__ codebook,
-    float *__restrict__ lut)
+    int64_t q, uint32_t *dyn)
 {
     __shared__ SelectShared sh;
     __shared__ unsigned long long codes_total;
-    extern __shared__ __attribute__((aligned(16))) uint32_t dyn[];
-    if ((int64_t)blockIdx.x >= nq) {   // (uniform) a table workgroup
-        const int64_t ql = (int64_t)blockIdx.x - nq;
-        lut_body<BLOCK>(Qt + ql * D, D, M, codebook, lut + ql * (int64_t)M * 256, reinterpret_cast<float *>(dyn));
-        return;
-    }
     const int PL = P * L;
     uint32_t *keys = dyn;
     int32_t *pid = reinterpret_cast<int32_t *>(dyn + PL);
     float *pd = reinterpret_cast<float *>(dyn + PL + P);
     float *pa = reinterpret_cast<float *>(dyn + PL + 2 * P);
-    const int64_t q = blockIdx.x;
     const float *row = Dt + q * ldt;
     for (int p = threadIdx.x; p < P; p += BLOCK) {
         const int32_t r = probe_id[q * P + p];
@@ -131,6 +124,26 @@ __global__ __launch_bounds__(BLOCK) void score_prune_kernel(
     if (mine) atomicAdd(&codes_total, mine);
     __syncthreads();
     if (threadIdx.x == 0 && n_scanned) n_scanned[q] = (int64_t)codes_total;
+}
+
+template <int BLOCK, int MAXV>
+__global__ __launch_bounds__(BLOCK) void score_prune_kernel(
+    const float *__restrict__ Dt, int64_t ldt, int64_t K, const int32_t *__restrict__ probe_id,
+    const float *__restrict__ probe_d, int P, int L, const int32_t *__restrict__ nbr,
+    const float *__restrict__ cst, const float *__restrict__ alpha, int S,
+    const uint4 *__restrict__ sub_info,
+    SubDesc *__restrict__ desc, int64_t *__restrict__ kept_sub, int64_t *__restrict__ n_scanned,
+    int64_t nq, const float *__restrict__ Qt, int D, int M, const float *__restrict__ codebook,
+    float *__restrict__ lut)
+{
+    extern __shared__ __attribute__((aligned(16))) uint32_t dyn[];
+    if ((int64_t)blockIdx.x >= nq) {   // (uniform) a table workgroup
+        const int64_t ql = (int64_t)blockIdx.x - nq;
+        lut_body<BLOCK>(Qt + ql * D, D, M, codebook, lut + ql * (int64_t)M * 256, reinterpret_cast<float *>(dyn));
+        return;
+    }
+    score_prune_body<BLOCK, MAXV>(Dt, ldt, K, probe_id, probe_d, P, L, nbr, cst, alpha, S, sub_info, desc, kept_sub, n_scanned,
+                                  blockIdx.x, dyn);
 }
 
 // Rotation in front of the product quantiser (Section 4: OPQ-compressed displacements, one global
