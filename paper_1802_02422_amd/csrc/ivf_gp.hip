@@ -504,9 +504,13 @@ int run_search(ivf_index *ix, const SearchArgs &a, const SearchPlan &pl, const L
         if ((rc = pack_rows(Q, n, D, nullptr, ws.qpk, ws.qn, ws.qsi, st))) return rc;
         if ((rc = launch_coarse(ws.qpk, ws.qn, ws.qsi, n, ix->cpk, ix->cnorm, ix->csi, K, Dp, ws.dt, ws.bm, st))) return rc;
         if ((rc = mark(1))) return rc;
-        // small batches: the selection runs inside the scoring launch (one workgroup per query does both)
+        // Where both are workgroups of 1024 threads with their keys in LDS, the selection runs inside the
+        // scoring launch (one workgroup per query does both): one kernel boundary less, and the selection
+        // of one query (LDS and ALU work) runs while the other workgroup of the CU waits for its gathers.
         const int nb = (int)((K + BMW - 1) / BMW);
-        const bool fused = n <= 2 * SKQ && P <= PS_P_MAX && nb <= PS_NB_MAX && PL > 4096;
+        // (nprobe * L <= 4096 keeps the two launches: its scoring kernel runs 256 threads a workgroup, and
+        // measured as one launch of 1024 it is slower: 1.33 against 0.44 + 0.85 ms on the 10^7-point workloads)
+        const bool fused = P <= PS_P_MAX && nb <= PS_NB_MAX && PL > 4096;
         if (!fused && (rc = launch_probe_select(ws.dt, ws.bm, n, K, P, pid, pd, st))) return rc;
         if ((rc = mark(2))) return rc;
 
