@@ -34,6 +34,11 @@ def test_small_deep_many_tiles(small):
     run_and_check(ix, Q, spec)
     run_and_check(ix, Q[:130], spec, nprobe=7, tau=1.0, k=1)
     run_and_check(ix, Q[:9], spec, nprobe=300, tau=0.05, k=300)
+    # nprobe * L > 4096 with nprobe <= 256: the selection runs inside the scoring launch; rows of probe ids that
+    # do not start on cache-line boundaries (190 x 4 bytes), a whole batch and a handful of queries
+    run_and_check(ix, Q, spec, nprobe=190, tau=0.3, k=50)
+    run_and_check(ix, Q[:5], spec, nprobe=190, tau=0.3, k=50)
+    run_and_check(ix, Q[:70], spec, nprobe=256, tau=0.1, k=10)
 
 
 def test_small_sift_like(small_sift):
